@@ -1,0 +1,211 @@
+/*
+ * flexdraft.h -- C ABI of the MI355X (gfx950) verify+draft hot path.
+ *
+ * One decoding step of the method runs a single target forward pass that
+ * verifies the previous draft and drafts the next block at once (paper,
+ * Sec. 4.1 "Inference").  This library provides the two operations of that
+ * pass that are not plain GEMMs:
+ *
+ *   fd_verify_draft_attn   hybrid-mask attention over a paged KV cache
+ *                          (Sec. 4.1 mask rules, Fig. 2b caption)
+ *   fd_accept_greedy       lossless acceptance, temperature -> 0 (Sec. 3)
+ *   fd_accept_sample       lossless acceptance by speculative sampling (Sec. 3)
+ *
+ * General conventions
+ *   - Plain C.  Every pointer marked "device" is a HIP device pointer on the
+ *     current device; pointers marked "host" are ordinary host memory.
+ *   - The caller owns every buffer.  The library never allocates or frees device
+ *     memory, never synchronises the stream, and never writes the KV cache.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL
+ *     is the default stream) and the call returns immediately.
+ *   - The return value is the only host-side error channel.  Argument errors are
+ *     detected on the host before anything is launched.  fd_last_error() returns
+ *     a thread-local description of the last failure.
+ *   - Device-side data that contradicts the host-side bounds (a kv_len above
+ *     max_kv_len, a page id outside [0, num_pages), a token id outside the
+ *     vocabulary, ...) is clamped by the kernels so that no access leaves the
+ *     caller's buffers, and the matching bit is OR-ed into *status if a status
+ *     word was supplied.  The numerical result of such a call is unspecified.
+ *
+ * Row convention (shared by all three calls)
+ *   Sequence i feeds n_i = k_i + m_i new rows into the pass: first k_i verify
+ *   rows (row 0 = the anchor, i.e. the previous step's bonus token, rows
+ *   1..k_i-1 = the drafted tokens being verified), then m_i mask-token rows (the
+ *   block being drafted).  Rows of all sequences are packed back to back.
+ */
+#ifndef FLEXDRAFT_H_
+#define FLEXDRAFT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+/* exported symbol */
+#define FD_API __attribute__((visibility("default")))
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fd_status {
+  FD_OK = 0,
+  FD_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent shapes        */
+  FD_ERR_UNSUPPORTED = 2,         /* a shape / dtype this build has no kernel for            */
+  FD_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below fd_*_workspace()                  */
+  FD_ERR_HIP = 4                  /* a HIP runtime call failed (launch error)                */
+} fd_status;
+
+typedef enum fd_dtype { FD_F32 = 0, FD_BF16 = 1 } fd_dtype;
+
+/* bits OR-ed into the optional device status word */
+#define FD_DEV_KV_LEN_RANGE   1u  /* kv_len[i] < 0 or > max_kv_len                           */
+#define FD_DEV_ROWS_RANGE     2u  /* n_i < 0, n_i > max_new_rows, k_i or v_i out of range    */
+#define FD_DEV_PAGE_RANGE     4u  /* page id outside [0, num_pages) or page list too short   */
+#define FD_DEV_TOKEN_RANGE    8u  /* token id outside [0, vocab)                             */
+
+/* fd_attn_args.flags */
+#define FD_ATTN_FORCE_GENERIC 1   /* use the scalar fp32-accumulate kernel even for bf16     */
+
+/*
+ * Arguments of fd_verify_draft_attn.
+ *
+ * Operation (Sec. 4.1; Fig. 2b caption).  For sequence i with L_i = kv_len[i]
+ * cached prefix tokens, keys are the L_i cached tokens followed by the n_i new
+ * rows.  New row r may look at
+ *     every cached token;
+ *     if r < k_i  (verify row): new rows t <= r        (causal; never a mask token)
+ *     if r >= k_i (mask row):   new rows t < v_i, and every mask row t >= k_i
+ *                               (its own block, both directions)
+ * where v_i = mask_vis[i] (default k_i) is the number of verify rows the block is
+ * conditioned on (the accepted-count hypothesis of Eq. 2).  The output row is
+ *     out[r,h] = sum_j softmax_j(sm_scale * q[r,h].k[j,h/G]) v[j,h/G]   over visible j,
+ * G = num_q_heads / num_kv_heads; lse[r,h] (optional) is the natural-log
+ * normaliser  log sum_j exp(sm_scale * q.k_j).
+ *
+ * Layouts (all innermost dimension = head_dim, contiguous):
+ *   q, out        [total_rows][num_q_heads][head_dim]        dense
+ *   k_new, v_new  [total_rows][num_kv_heads][head_dim]       dense; NOT appended to the cache
+ *   k_cache, v_cache: element (page p, kv head g, slot s, d) at
+ *       p*cache_stride_page + g*cache_stride_head + s*cache_stride_token + d
+ *     strides in elements, each a multiple of 8.  A contiguous cache is the case
+ *     page_indices = 0,1,2,...
+ *   page_indices[page_indptr[i] .. page_indptr[i+1])  physical pages of sequence i,
+ *     in logical order; token p of the sequence lives in page p / page_size,
+ *     slot p % page_size.
+ *   row_indptr[i] .. row_indptr[i+1]  packed rows of sequence i.
+ * dtype applies to q, k_new, v_new, k_cache, v_cache and out.
+ */
+typedef struct fd_attn_args {
+  int32_t batch;              /* B >= 0                                                       */
+  int32_t num_q_heads;        /* Hq, multiple of num_kv_heads                                 */
+  int32_t num_kv_heads;       /* Hkv                                                          */
+  int32_t head_dim;           /* D: multiple of 8, <= 128 (MFMA kernel: 128)                  */
+  int32_t page_size;          /* tokens per page, >= 1 (MFMA kernel: multiple of 16)          */
+  int32_t dtype;              /* fd_dtype                                                     */
+  float   sm_scale;           /* 0 => 1/sqrt(head_dim)                                        */
+  int32_t flags;              /* FD_ATTN_*                                                    */
+  /* host-side bounds that fix the launch shape (no device read-back is needed) */
+  int32_t total_rows;         /* R = row_indptr[B]                                            */
+  int32_t max_kv_len;         /* >= every kv_len[i]                                           */
+  int32_t max_new_rows;       /* >= every n_i                                                 */
+  int32_t num_pages;          /* physical pages in the pool; page ids are checked against it  */
+  int32_t kv_chunk;           /* cached tokens per work-group, multiple of 64; 0 => automatic */
+  int32_t reserved;
+  const void *k_cache;        /* device                                                       */
+  const void *v_cache;        /* device                                                       */
+  int64_t cache_stride_page, cache_stride_head, cache_stride_token;
+  const int32_t *page_indptr; /* device [B+1]                                                 */
+  const int32_t *page_indices;/* device [page_indptr[B]]                                      */
+  const int32_t *kv_len;      /* device [B]                                                   */
+  const int32_t *row_indptr;  /* device [B+1]                                                 */
+  const int32_t *verify_len;  /* device [B]   k_i in [0, n_i]                                 */
+  const int32_t *mask_vis;    /* device [B] or NULL (=> v_i = k_i); 0 <= v_i <= k_i           */
+  const void *q;              /* device                                                       */
+  const void *k_new;          /* device                                                       */
+  const void *v_new;          /* device                                                       */
+  void  *out;                 /* device                                                       */
+  float *lse;                 /* device [total_rows][num_q_heads] or NULL                     */
+  void  *workspace;           /* device, 256-byte aligned, >= fd_verify_draft_attn_workspace  */
+  size_t workspace_bytes;
+  uint32_t *status;           /* device uint32[1] or NULL; caller zeroes it                   */
+} fd_attn_args;
+
+/* Bytes of workspace fd_verify_draft_attn needs for these arguments (reads only the
+ * host-side scalar fields).  Pure host function; returns 0 on invalid arguments. */
+FD_API size_t fd_verify_draft_attn_workspace(const fd_attn_args *args);
+
+/* Hybrid-mask verify+draft attention (Sec. 4.1).  Asynchronous on hip_stream.
+ * Errors: FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE_TOO_SMALL, FD_ERR_HIP. */
+FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream);
+
+/*
+ * Greedy lossless acceptance (Sec. 3, temperature -> 0).
+ *
+ * target_logits  device [total_rows][row_stride] of dtype dt; only the first
+ *                `vocab` entries of a row are read.  Rows are the verify rows of
+ *                all sequences, packed; row_indptr[B+1] (device) delimits them.
+ * input_tokens   device [total_rows]: the token fed at each verify row.
+ * For every row j:  a_j = lowest index attaining max_v target_logits[j][v].
+ * For sequence i with k_i rows: accept_len[i] = r_i = number of leading
+ * j in [0, k_i-2] with a_j == input_tokens[j+1]; bonus_token[i] = a_{r_i}.
+ * The step commits r_i + 1 tokens.  k_i = 0 gives accept_len 0, bonus -1.
+ * row_argmax     device [total_rows] or NULL: receives every a_j.
+ * Values are compared exactly as stored; NaN logits are undefined.
+ */
+FD_API fd_status fd_accept_greedy(const void *target_logits, fd_dtype dt, int64_t row_stride, int32_t vocab,
+                           const int32_t *row_indptr, const int32_t *input_tokens,
+                           int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                           int32_t *accept_len, int32_t *bonus_token, int32_t *row_argmax,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Speculative-sampling acceptance with caller-supplied uniforms (Sec. 3).
+ *
+ * p_j = softmax(target_logits[j] / temperature), q_j = softmax(draft_logits[j] /
+ * temperature); draft row j is the distribution the token fed at row j+1 was drawn
+ * from (each sequence's last draft row is not read).  For j = 0 .. k_i-2 with
+ * d = input_tokens[j+1]: keep d iff u_accept[j] * q_j(d) < p_j(d); stop at the first
+ * row j* that fails.  The bonus token is drawn from the residual
+ * max(0, p_j* - q_j*) (from p_{k_i-1} when every draft was kept; from p_j* if the
+ * residual is identically zero) by inverse CDF in ascending token order: the first
+ * token whose inclusive cumulative weight exceeds u_resample[j*] * total weight.
+ * accept_len[i] = j*.  u_accept, u_resample: device [total_rows] float in [0,1).
+ * Sums are accumulated in fp64 from fp32 exponentials; a decision whose exact
+ * margin is below about 1e-6 (relative) may fall on either side.
+ */
+FD_API fd_status fd_accept_sample(const void *target_logits, const void *draft_logits, fd_dtype dt,
+                           int64_t row_stride, int32_t vocab, float temperature,
+                           const int32_t *row_indptr, const int32_t *input_tokens,
+                           const float *u_accept, const float *u_resample,
+                           int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                           int32_t *accept_len, int32_t *bonus_token,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Workspace bytes for the acceptance calls (sampling != 0 for fd_accept_sample); 0 on invalid arguments. */
+FD_API size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling);
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+FD_API const char *fd_last_error(void);
+
+/*
+ * Kernel timing for benchmarks.  fd_profile_begin(n) creates 2n HIP events; while
+ * profiling is on, each fd_verify_draft_attn call records one (start, stop) pair
+ * around its main streaming kernel on the call's stream (calls beyond n are not
+ * recorded).  fd_profile_end synchronises the recorded events, writes up to
+ * `capacity` durations in milliseconds to ms_out (host), destroys the events and
+ * returns the number written.  Not thread-safe; off by default.
+ */
+FD_API fd_status fd_profile_begin(int32_t max_calls);
+FD_API int32_t   fd_profile_end(float *ms_out, int32_t capacity);
+
+/* Plain device-to-device streaming copy of `bytes` (multiple of 16, both pointers 16-byte
+ * aligned), asynchronous on hip_stream.  It exists for measurement: the achievable-bandwidth
+ * yard-stick, and the known-size kernel the HBM traffic counters are scaled against. */
+FD_API fd_status fd_stream_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
+/* Library version string, e.g. "flexdraft-gfx950 0.1". */
+FD_API const char *fd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXDRAFT_H_ */

@@ -1,0 +1,544 @@
+// Lossless acceptance kernels (Sec. 3): greedy arg-max / longest matching prefix / bonus
+// token, and the speculative-sampling variant with supplied uniforms.
+//
+// Both are one streaming pass over [rows][vocab] logits, so the vocabulary of every row
+// is cut into segments and one work-group reduces one (row, segment); a small epilogue
+// per sequence merges the segment results and walks the verify rows.
+#include "fd_common.h"
+#include <float.h>
+
+namespace fd {
+
+constexpr int ACC_BLOCK = 256;
+
+// 8 consecutive logits starting at element `e` of a row (e multiple of 8) as floats;
+// entries at or beyond `vocab` come back as -inf.  `vec_ok` says the row base is 16-byte
+// aligned so that one 16-byte load per lane can be used.
+template <typename T>
+__device__ __forceinline__ void load8(const T* row, int e, int vocab, bool vec_ok, float (&x)[8]);
+
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const bf16_t* row, int e, int vocab, bool vec_ok, float (&x)[8]) {
+  if (vec_ok && e + 8 <= vocab) {
+    u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + e));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (e + i < vocab) ? bf16_to_f32(row[e + i]) : -INFINITY;
+  }
+}
+
+template <>
+__device__ __forceinline__ void load8<float>(const float* row, int e, int vocab, bool vec_ok, float (&x)[8]) {
+  if (vec_ok && e + 8 <= vocab) {
+    f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + e));
+    f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + e + 4));
+    x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3];
+    x[4] = b[0]; x[5] = b[1]; x[6] = b[2]; x[7] = b[3];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (e + i < vocab) ? row[e + i] : -INFINITY;
+  }
+}
+
+// (value, index) with "larger value wins, equal values: lower index wins"
+__device__ __forceinline__ void amax_merge(float& v, int& i, float ov, int oi) {
+  if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+}
+
+// ---------------------------------------------------------------------------------------
+// Greedy, pass 1: arg-max of one vocabulary segment of one row.
+//   grid (segments, rows); part_val/part_idx [rows][segments]
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ACC_BLOCK) void argmax_partial_kernel(
+    const T* __restrict__ logits, long long row_stride, int vocab, int seg_len,
+    float* __restrict__ part_val, int* __restrict__ part_idx) {
+  const int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
+  const T* rp = logits + (long long)row * row_stride;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(rp) & 15) == 0;
+  const int e0 = seg * seg_len;
+  const int e1 = min(vocab, e0 + seg_len);
+  float bv = -INFINITY; int bi = 0x7fffffff;
+  for (int e = e0 + threadIdx.x * 8; e < e1; e += ACC_BLOCK * 8) {
+    float x[8];
+    load8<T>(rp, e, e1, vec_ok, x);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (e + i < e1) amax_merge(bv, bi, x[i], e + i);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    float ov = __shfl_xor(bv, off); int oi = __shfl_xor(bi, off);
+    amax_merge(bv, bi, ov, oi);
+  }
+  __shared__ float sv[ACC_BLOCK / FD_WAVE]; __shared__ int si[ACC_BLOCK / FD_WAVE];
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) amax_merge(bv, bi, sv[w], si[w]);
+    part_val[(long long)row * nseg + seg] = bv;
+    part_idx[(long long)row * nseg + seg] = bi;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Greedy, pass 2: one wave per sequence.  Merge the segment results of each verify row,
+// then count the leading rows whose arg-max equals the token fed at the next row.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(FD_WAVE) void accept_greedy_epilogue_kernel(
+    const float* __restrict__ part_val, const int* __restrict__ part_idx, int nseg,
+    const int* __restrict__ row_indptr, const int* __restrict__ input_tokens,
+    int total_rows, int max_rows_per_seq,
+    int* __restrict__ accept_len, int* __restrict__ bonus_token, int* __restrict__ row_argmax) {
+  const int seq = blockIdx.x, lane = threadIdx.x;
+  int r0 = clampi(row_indptr[seq], 0, total_rows);
+  int k = clampi(row_indptr[seq + 1] - r0, 0, min(max_rows_per_seq, total_rows - r0));
+  if (k == 0) { if (lane == 0) { accept_len[seq] = 0; bonus_token[seq] = -1; } return; }
+  // first mismatching row (k-1 if none); rows handled 64 at a time, in order
+  int first_bad = k - 1, bonus = -1;
+  bool done = false;
+  for (int base = 0; base < k && !done; base += FD_WAVE) {
+    int j = base + lane;
+    int a = -1; bool bad = false;
+    if (j < k) {
+      float bv = -INFINITY; int bi = 0x7fffffff;
+      for (int s = 0; s < nseg; ++s)
+        amax_merge(bv, bi, part_val[(long long)(r0 + j) * nseg + s], part_idx[(long long)(r0 + j) * nseg + s]);
+      a = bi;
+      if (row_argmax) row_argmax[r0 + j] = a;
+      bad = (j == k - 1) || (a != input_tokens[r0 + j + 1]);
+    }
+    unsigned long long m = __ballot(bad);
+    if (m && !done) {
+      int src = __ffsll((long long)m) - 1;
+      first_bad = base + src;
+      bonus = __shfl(a, src);
+      done = true;
+      // keep filling row_argmax for the remaining rows if it was requested
+      if (row_argmax) {
+        for (int b2 = base + FD_WAVE; b2 < k; b2 += FD_WAVE) {
+          int j2 = b2 + lane;
+          if (j2 < k) {
+            float bv = -INFINITY; int bi = 0x7fffffff;
+            for (int s = 0; s < nseg; ++s)
+              amax_merge(bv, bi, part_val[(long long)(r0 + j2) * nseg + s], part_idx[(long long)(r0 + j2) * nseg + s]);
+            row_argmax[r0 + j2] = bi;
+          }
+        }
+      }
+    }
+  }
+  if (lane == 0) { accept_len[seq] = first_bad; bonus_token[seq] = bonus; }
+}
+
+// ---------------------------------------------------------------------------------------
+// Sampling, pass 1: per (row, segment) the maximum and the sum of exponentials of the
+// temperature-scaled target and draft logits.  part [rows][segments][4] doubles:
+// (max_t, sum_t, max_d, sum_d) with sum = sum exp(x*invT - max).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  return v;
+}
+
+// One streaming pass with a running maximum: (m, s) with s = sum exp(x*invT - m), rescaled
+// whenever the maximum grows; thread results are merged the same way.
+template <typename T>
+__device__ __forceinline__ void segment_max_sum(const T* rp, int e0, int e1, float inv_t, bool vec_ok,
+                                                float* s_red, double* d_red, double& out_max, double& out_sum) {
+  float m = -INFINITY; double s = 0.0;
+  for (int e = e0 + threadIdx.x * 8; e < e1; e += ACC_BLOCK * 8) {
+    float x[8]; load8<T>(rp, e, e1, vec_ok, x);
+    float m8 = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { x[i] *= inv_t; m8 = fmaxf(m8, x[i]); }   // padding stays -inf (invT > 0)
+    if (m8 > m) { s *= (double)expf(m - m8); m = m8; }
+    if (m > -INFINITY) {
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part += expf(x[i] - m);
+      s += (double)part;
+    }
+  }
+  const float wm = wave_max(m);
+  double ws = (m > -INFINITY) ? s * exp((double)m - (double)wm) : 0.0;
+  ws = wave_sum(ws);
+  if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = wm; d_red[threadIdx.x >> 6] = ws; }
+  __syncthreads();
+  float bm = s_red[0];
+  for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) bm = fmaxf(bm, s_red[w]);
+  double bs = 0.0;
+  for (int w = 0; w < ACC_BLOCK / FD_WAVE; ++w)
+    if (s_red[w] > -INFINITY) bs += d_red[w] * exp((double)s_red[w] - (double)bm);
+  __syncthreads();
+  out_max = (double)bm; out_sum = bs;
+}
+
+template <typename T>
+__global__ __launch_bounds__(ACC_BLOCK) void softmax_stats_partial_kernel(
+    const T* __restrict__ target, const T* __restrict__ draft, long long row_stride, int vocab, int seg_len,
+    float inv_t, double* __restrict__ part) {
+  __shared__ float s_red[ACC_BLOCK / FD_WAVE]; __shared__ double d_red[ACC_BLOCK / FD_WAVE];
+  const int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
+  const int e0 = seg * seg_len, e1 = min(vocab, e0 + seg_len);
+  const T* tp = target + (long long)row * row_stride;
+  const T* dp = draft + (long long)row * row_stride;
+  double mt, st, md, sd;
+  segment_max_sum<T>(tp, e0, e1, inv_t, (reinterpret_cast<uintptr_t>(tp) & 15) == 0, s_red, d_red, mt, st);
+  segment_max_sum<T>(dp, e0, e1, inv_t, (reinterpret_cast<uintptr_t>(dp) & 15) == 0, s_red, d_red, md, sd);
+  if (threadIdx.x == 0) {
+    double* o = part + ((long long)row * nseg + seg) * 4;
+    o[0] = mt; o[1] = st; o[2] = md; o[3] = sd;
+  }
+}
+
+// Merge the segment statistics of one row (all lanes of a wave take part): returns the
+// row maximum M (scaled units) and Z = sum exp(x*invT - M), for target (0) or draft (2).
+__device__ __forceinline__ void merge_row_stats(const double* part_row, int nseg, int which, int lane,
+                                                double& M, double& Z) {
+  double m = -INFINITY;
+  for (int s = lane; s < nseg; s += FD_WAVE) m = fmax(m, part_row[s * 4 + which]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmax(m, __shfl_xor(m, off));
+  double z = 0.0;
+  for (int s = lane; s < nseg; s += FD_WAVE) {
+    double ms = part_row[s * 4 + which], ss = part_row[s * 4 + which + 1];
+    if (ss > 0.0) z += ss * exp(ms - m);
+  }
+  z = wave_sum(z);
+  M = m; Z = z;
+}
+
+// ---------------------------------------------------------------------------------------
+// Sampling, pass 2: grid (chunk groups, sequences).  Every work-group first repeats the
+// (cheap) accept tests of its sequence to find the stopping row j*, then sums the bonus
+// token's weights -- residual max(0,p-q), and p itself -- over its share of the
+// vocabulary, one double per 512-token chunk (one wave, 8 tokens per lane).
+//   decision [B][4] int: (stop row, rejected?, -, -) written by group 0
+//   chunk_res, chunk_p [B][nchunks] doubles
+// ---------------------------------------------------------------------------------------
+constexpr int CHUNK_TOK = FD_WAVE * 8;   // 512 tokens per chunk
+
+template <typename T>
+__global__ __launch_bounds__(ACC_BLOCK) void accept_sample_weights_kernel(
+    const T* __restrict__ target, const T* __restrict__ draft, long long row_stride, int vocab, float inv_t,
+    const double* __restrict__ part, int nseg,
+    const int* __restrict__ row_indptr, const int* __restrict__ input_tokens,
+    const float* __restrict__ u_accept, int total_rows, int max_rows_per_seq, int nchunks,
+    int* __restrict__ decision, double* __restrict__ row_stats /*[B][4]*/,
+    double* __restrict__ chunk_res, double* __restrict__ chunk_p) {
+  const int seq = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int NW = ACC_BLOCK / FD_WAVE;
+  int r0 = clampi(row_indptr[seq], 0, total_rows);
+  int k = clampi(row_indptr[seq + 1] - r0, 0, min(max_rows_per_seq, total_rows - r0));
+  if (k == 0) { if (grp == 0 && threadIdx.x == 0) { decision[seq * 4] = -1; decision[seq * 4 + 1] = 0; } return; }
+
+  __shared__ int s_first_bad;
+  __shared__ double s_stats[4];
+  if (threadIdx.x == 0) s_first_bad = k - 1;
+  __syncthreads();
+  // accept tests, rows distributed over the waves; every wave evaluates whole rows
+  for (int j = wave; j < k - 1; j += NW) {
+    if (j > *(volatile int*)&s_first_bad) break;      // monotone shortcut: later rows cannot matter
+    const double* pr = part + (long long)(r0 + j) * nseg * 4;
+    double Mt, Zt, Md, Zd;
+    merge_row_stats(pr, nseg, 0, lane, Mt, Zt);
+    merge_row_stats(pr, nseg, 2, lane, Md, Zd);
+    if (lane == 0) {
+      int d = input_tokens[r0 + j + 1];
+      bool keep = false;
+      if (d >= 0 && d < vocab) {
+        float xt = Elem<T>::load(target + (long long)(r0 + j) * row_stride + d);
+        float xd = Elem<T>::load(draft + (long long)(r0 + j) * row_stride + d);
+        double p = (double)expf(xt * inv_t - (float)Mt) / Zt;
+        double q = (double)expf(xd * inv_t - (float)Md) / Zd;
+        keep = (double)u_accept[r0 + j] * q < p;
+      }
+      if (!keep) atomicMin(&s_first_bad, j);
+    }
+  }
+  __syncthreads();
+  const int stop = s_first_bad;
+  const bool rejected = stop < k - 1 ? true : false;   // stop == k-1 only when every draft was kept
+  // (a rejection at row k-1 cannot happen: that row has no draft to test)
+  if (wave == 0) {
+    const double* pr = part + (long long)(r0 + stop) * nseg * 4;
+    double Mt, Zt, Md, Zd;
+    merge_row_stats(pr, nseg, 0, lane, Mt, Zt);
+    merge_row_stats(pr, nseg, 2, lane, Md, Zd);
+    if (lane == 0) { s_stats[0] = Mt; s_stats[1] = Zt; s_stats[2] = Md; s_stats[3] = Zd; }
+  }
+  __syncthreads();
+  const float Mt = (float)s_stats[0], Md = (float)s_stats[2];
+  const double iZt = 1.0 / s_stats[1], iZd = 1.0 / s_stats[3];
+  if (grp == 0 && threadIdx.x == 0) {
+    decision[seq * 4] = stop; decision[seq * 4 + 1] = rejected ? 1 : 0;
+    row_stats[seq * 4 + 0] = s_stats[0]; row_stats[seq * 4 + 1] = s_stats[1];
+    row_stats[seq * 4 + 2] = s_stats[2]; row_stats[seq * 4 + 3] = s_stats[3];
+  }
+  const T* tp = target + (long long)(r0 + stop) * row_stride;
+  const T* dp = draft + (long long)(r0 + stop) * row_stride;
+  const bool vt = (reinterpret_cast<uintptr_t>(tp) & 15) == 0, vd = (reinterpret_cast<uintptr_t>(dp) & 15) == 0;
+  for (int c = grp * NW + wave; c < nchunks; c += ngrp * NW) {
+    int e = c * CHUNK_TOK + lane * 8;
+    double wres = 0.0, wp = 0.0;
+    if (e < vocab) {
+      float xt[8], xd[8];
+      load8<T>(tp, e, vocab, vt, xt);
+      load8<T>(dp, e, vocab, vd, xd);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        double p = (double)expf(xt[i] * inv_t - Mt) * iZt;
+        double q = (double)expf(xd[i] * inv_t - Md) * iZd;
+        wp += p;
+        wres += fmax(0.0, p - q);
+      }
+    }
+    wres = wave_sum(wres); wp = wave_sum(wp);
+    if (lane == 0) { chunk_res[(long long)seq * nchunks + c] = wres; chunk_p[(long long)seq * nchunks + c] = wp; }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Sampling, pass 3: one work-group per sequence.  Scan the chunk sums, find the chunk the
+// scaled uniform falls into, then scan that chunk's 512 tokens with one wave.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ACC_BLOCK) void accept_sample_pick_kernel(
+    const T* __restrict__ target, const T* __restrict__ draft, long long row_stride, int vocab, float inv_t,
+    const int* __restrict__ row_indptr, const float* __restrict__ u_resample, int total_rows,
+    int nchunks, const int* __restrict__ decision, const double* __restrict__ row_stats,
+    const double* __restrict__ chunk_res, const double* __restrict__ chunk_p,
+    int* __restrict__ accept_len, int* __restrict__ bonus_token) {
+  const int seq = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int NW = ACC_BLOCK / FD_WAVE;
+  const int stop = decision[seq * 4];
+  if (stop < 0) { if (threadIdx.x == 0) { accept_len[seq] = 0; bonus_token[seq] = -1; } return; }
+  const int r0 = clampi(row_indptr[seq], 0, total_rows);
+  const bool rejected = decision[seq * 4 + 1] != 0;
+  __shared__ double s_wsum[NW];
+  __shared__ double s_tot[2];
+  __shared__ int s_chunk; __shared__ double s_prefix;
+
+  // totals of both weightings
+  double a = 0.0, b = 0.0;
+  for (int c = threadIdx.x; c < nchunks; c += ACC_BLOCK) { a += chunk_res[(long long)seq * nchunks + c]; b += chunk_p[(long long)seq * nchunks + c]; }
+  a = wave_sum(a);
+  if (lane == 0) s_wsum[wave] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) { double t = 0; for (int w = 0; w < NW; ++w) t += s_wsum[w]; s_tot[0] = t; }
+  __syncthreads();
+  b = wave_sum(b);
+  if (lane == 0) s_wsum[wave] = b;
+  __syncthreads();
+  if (threadIdx.x == 0) { double t = 0; for (int w = 0; w < NW; ++w) t += s_wsum[w]; s_tot[1] = t; }
+  __syncthreads();
+  const bool use_res = rejected && s_tot[0] > 0.0;      // residual identically zero -> draw from p
+  const double* cw = (use_res ? chunk_res : chunk_p) + (long long)seq * nchunks;
+  const double W = use_res ? s_tot[0] : s_tot[1];
+  const double thr = (double)u_resample[r0 + stop] * W;
+
+  // ordered scan over chunks by wave 0 (chunk counts are a few hundred)
+  if (wave == 0) {
+    double run = 0.0; int found = -1; double pre = 0.0;
+    for (int base = 0; base < nchunks && found < 0; base += FD_WAVE) {
+      int c = base + lane;
+      double w = c < nchunks ? cw[c] : 0.0;
+      double inc = w;                                   // inclusive scan across lanes
+#pragma unroll
+      for (int off = 1; off < FD_WAVE; off <<= 1) { double o = __shfl_up(inc, off); if (lane >= off) inc += o; }
+      bool hit = c < nchunks && (run + inc > thr);
+      unsigned long long m = __ballot(hit);
+      if (m) {
+        int src = __ffsll((long long)m) - 1;
+        found = base + src;
+        pre = run + __shfl(inc, src) - __shfl(w, src);
+      }
+      run += __shfl(inc, FD_WAVE - 1);
+    }
+    if (found < 0) {                                    // rounding corner: take the last non-empty chunk
+      pre = 0.0; run = 0.0;
+      for (int c = 0; c < nchunks; ++c) { double w = cw[c]; if (w > 0.0) { found = c; pre = run; } run += w; }
+      if (found < 0) found = 0;
+    }
+    if (lane == 0) { s_chunk = found; s_prefix = pre; }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  const int c = s_chunk;
+  const float Mt = (float)row_stats[seq * 4 + 0], Md = (float)row_stats[seq * 4 + 2];
+  const double iZt = 1.0 / row_stats[seq * 4 + 1], iZd = 1.0 / row_stats[seq * 4 + 3];
+  const T* tp = target + (long long)(r0 + stop) * row_stride;
+  const T* dp = draft + (long long)(r0 + stop) * row_stride;
+  const bool vt = (reinterpret_cast<uintptr_t>(tp) & 15) == 0, vd = (reinterpret_cast<uintptr_t>(dp) & 15) == 0;
+  const int e = c * CHUNK_TOK + lane * 8;
+  double w8[8]; double lsum = 0.0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w8[i] = 0.0;
+  if (e < vocab) {
+    float xt[8], xd[8];
+    load8<T>(tp, e, vocab, vt, xt);
+    load8<T>(dp, e, vocab, vd, xd);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      double p = (double)expf(xt[i] * inv_t - Mt) * iZt;
+      double q = (double)expf(xd[i] * inv_t - Md) * iZd;
+      w8[i] = use_res ? fmax(0.0, p - q) : p;
+      lsum += w8[i];
+    }
+  }
+  double inc = lsum;
+#pragma unroll
+  for (int off = 1; off < FD_WAVE; off <<= 1) { double o = __shfl_up(inc, off); if (lane >= off) inc += o; }
+  double before = s_prefix + inc - lsum;
+  int pick = -1;
+  if (before + lsum > thr) {                            // the threshold is crossed inside this lane (or earlier)
+    double run = before;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { run += w8[i]; if (pick < 0 && run > thr && w8[i] > 0.0) pick = e + i; }
+  }
+  unsigned long long m = __ballot(pick >= 0);
+  int result;
+  if (m) {
+    result = __shfl(pick, __ffsll((long long)m) - 1);
+  } else {                                              // rounding corner: last token of the chunk with weight
+    int last = -1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) if (w8[i] > 0.0) last = e + i;
+    unsigned long long m2 = __ballot(last >= 0);
+    result = m2 ? __shfl(last, 63 - __clzll((long long)m2)) : min(vocab - 1, c * CHUNK_TOK);
+  }
+  if (lane == 0) { accept_len[seq] = stop; bonus_token[seq] = result; }
+}
+
+// ---------------------------------------------------------------------------------------
+// host-side launchers (called from api.hip)
+// ---------------------------------------------------------------------------------------
+static inline int pick_segments(int rows, int vocab) {
+  // enough work-groups to cover the chip a few times, but at least 4096 logits per group
+  int want = (2048 + rows - 1) / (rows > 0 ? rows : 1);
+  int cap = (vocab + 4095) / 4096;
+  int s = want < 1 ? 1 : want;
+  if (s > cap) s = cap;
+  if (s > 64) s = 64;
+  if (s < 1) s = 1;
+  return s;
+}
+static inline int seg_len_for(int vocab, int nseg) {
+  int l = (vocab + nseg - 1) / nseg;
+  return (l + 7) / 8 * 8;
+}
+
+// Sampling workspace layout (all blocks 256-byte aligned), shared by the size query and the launcher.
+struct SampleLayout {
+  size_t part, row_stats, chunk_res, chunk_p, decision, total;
+  int nseg, nchunks;
+};
+static inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+static inline SampleLayout sample_layout(int batch, int total_rows, int vocab) {
+  SampleLayout l;
+  size_t rows = (size_t)(total_rows > 0 ? total_rows : 1), seqs = (size_t)(batch > 0 ? batch : 1);
+  l.nseg = pick_segments(total_rows, vocab);
+  l.nchunks = (vocab + CHUNK_TOK - 1) / CHUNK_TOK;
+  size_t off = 0;
+  l.part = off;      off += align256(rows * l.nseg * 4 * sizeof(double));
+  l.row_stats = off; off += align256(seqs * 4 * sizeof(double));
+  l.chunk_res = off; off += align256(seqs * l.nchunks * sizeof(double));
+  l.chunk_p = off;   off += align256(seqs * l.nchunks * sizeof(double));
+  l.decision = off;  off += align256(seqs * 4 * sizeof(int));
+  l.total = off;
+  return l;
+}
+
+size_t accept_workspace_bytes(int batch, int total_rows, int vocab, int sampling) {
+  if (batch < 0 || total_rows < 0 || vocab <= 0) return 0;
+  if (sampling) return sample_layout(batch, total_rows, vocab).total;
+  size_t rows = (size_t)(total_rows > 0 ? total_rows : 1);
+  return align256(rows * pick_segments(total_rows, vocab) * (sizeof(float) + sizeof(int)));
+}
+
+template <typename T>
+static hipError_t launch_greedy(const T* logits, long long row_stride, int vocab, const int* row_indptr,
+                                const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
+                                int* bonus, int* row_argmax, void* ws, hipStream_t st) {
+  int nseg = pick_segments(total_rows, vocab);
+  int sl = seg_len_for(vocab, nseg);
+  float* pv = reinterpret_cast<float*>(ws);
+  int* pi = reinterpret_cast<int*>(pv + (size_t)(total_rows > 0 ? total_rows : 1) * nseg);
+  if (total_rows > 0)
+    hipLaunchKernelGGL(argmax_partial_kernel<T>, dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
+                       logits, row_stride, vocab, sl, pv, pi);
+  if (batch > 0)
+    hipLaunchKernelGGL(accept_greedy_epilogue_kernel, dim3(batch), dim3(FD_WAVE), 0, st,
+                       pv, pi, nseg, row_indptr, toks, total_rows, max_rows, accept_len, bonus, row_argmax);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_sample(const T* target, const T* draft, long long row_stride, int vocab, float temperature,
+                                const int* row_indptr, const int* toks, const float* ua, const float* ur,
+                                int batch, int total_rows, int max_rows, int* accept_len, int* bonus,
+                                void* ws, hipStream_t st) {
+  const SampleLayout lay = sample_layout(batch, total_rows, vocab);
+  const int nseg = lay.nseg, nchunks = lay.nchunks;
+  const int sl = seg_len_for(vocab, nseg);
+  char* base = reinterpret_cast<char*>(ws);
+  double* part = reinterpret_cast<double*>(base + lay.part);
+  double* row_stats = reinterpret_cast<double*>(base + lay.row_stats);
+  double* chunk_res = reinterpret_cast<double*>(base + lay.chunk_res);
+  double* chunk_p = reinterpret_cast<double*>(base + lay.chunk_p);
+  int* decision = reinterpret_cast<int*>(base + lay.decision);
+  float inv_t = 1.0f / temperature;
+  if (total_rows > 0)
+    hipLaunchKernelGGL(softmax_stats_partial_kernel<T>, dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
+                       target, draft, row_stride, vocab, sl, inv_t, part);
+  if (batch > 0) {
+    int groups = (nchunks + (ACC_BLOCK / FD_WAVE) - 1) / (ACC_BLOCK / FD_WAVE);
+    int want = (1024 + batch - 1) / batch;
+    if (groups > want) groups = want;
+    if (groups < 1) groups = 1;
+    hipLaunchKernelGGL(accept_sample_weights_kernel<T>, dim3(groups, batch), dim3(ACC_BLOCK), 0, st,
+                       target, draft, row_stride, vocab, inv_t, part, nseg, row_indptr, toks, ua,
+                       total_rows, max_rows, nchunks, decision, row_stats, chunk_res, chunk_p);
+    hipLaunchKernelGGL(accept_sample_pick_kernel<T>, dim3(batch), dim3(ACC_BLOCK), 0, st,
+                       target, draft, row_stride, vocab, inv_t, row_indptr, ur, total_rows, nchunks,
+                       decision, row_stats, chunk_res, chunk_p, accept_len, bonus);
+  }
+  return hipGetLastError();
+}
+
+hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,
+                             const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
+                             int* bonus, int* row_argmax, void* ws, hipStream_t st) {
+  if (dt == FD_BF16)
+    return launch_greedy<bf16_t>((const bf16_t*)logits, row_stride, vocab, row_indptr, toks, batch, total_rows,
+                                 max_rows, accept_len, bonus, row_argmax, ws, st);
+  return launch_greedy<float>((const float*)logits, row_stride, vocab, row_indptr, toks, batch, total_rows,
+                              max_rows, accept_len, bonus, row_argmax, ws, st);
+}
+
+hipError_t run_accept_sample(const void* target, const void* draft, int dt, long long row_stride, int vocab,
+                             float temperature, const int* row_indptr, const int* toks, const float* ua,
+                             const float* ur, int batch, int total_rows, int max_rows, int* accept_len,
+                             int* bonus, void* ws, hipStream_t st) {
+  if (dt == FD_BF16)
+    return launch_sample<bf16_t>((const bf16_t*)target, (const bf16_t*)draft, row_stride, vocab, temperature,
+                                 row_indptr, toks, ua, ur, batch, total_rows, max_rows, accept_len, bonus, ws, st);
+  return launch_sample<float>((const float*)target, (const float*)draft, row_stride, vocab, temperature,
+                              row_indptr, toks, ua, ur, batch, total_rows, max_rows, accept_len, bonus, ws, st);
+}
+
+}  // namespace fd

@@ -1,0 +1,270 @@
+// C ABI of the library: argument validation, launch-shape decisions, workspace layout.
+// Every entry point is declared and documented in include/flexdraft.h.
+#include "fd_common.h"
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+namespace fd {
+hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
+hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, hipStream_t st);
+hipError_t run_attn_mfma(const AttnParams& p, hipStream_t st);
+size_t accept_workspace_bytes(int batch, int total_rows, int vocab, int sampling);
+hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,
+                             const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
+                             int* bonus, int* row_argmax, void* ws, hipStream_t st);
+hipError_t run_accept_sample(const void* target, const void* draft, int dt, long long row_stride, int vocab,
+                             float temperature, const int* row_indptr, const int* toks, const float* ua,
+                             const float* ur, int batch, int total_rows, int max_rows, int* accept_len,
+                             int* bonus, void* ws, hipStream_t st);
+hipError_t run_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+}  // namespace fd
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fd_status fail(fd_status code, const char* fmt, ...) {
+  va_list ap; va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// profiling state (fd_profile_begin / fd_profile_end)
+hipEvent_t* g_prof_events = nullptr;
+int g_prof_cap = 0, g_prof_used = 0;
+
+struct AttnPlan {
+  bool use_mfma;
+  int chunk, max_chunks, row_tiles;
+  size_t acc_bytes, ml_bytes, total_bytes;
+};
+
+// Host-only checks of the scalar fields and the launch-shape plan.
+fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
+  if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
+  if (a->batch < 0 || a->total_rows < 0 || a->max_kv_len < 0 || a->max_new_rows < 0 || a->num_pages < 0)
+    return fail(FD_ERR_INVALID_ARG, "negative size (batch %d, total_rows %d, max_kv_len %d, max_new_rows %d, num_pages %d)",
+                a->batch, a->total_rows, a->max_kv_len, a->max_new_rows, a->num_pages);
+  if (a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->num_q_heads % a->num_kv_heads)
+    return fail(FD_ERR_INVALID_ARG, "num_q_heads %d must be a positive multiple of num_kv_heads %d", a->num_q_heads, a->num_kv_heads);
+  if (a->head_dim <= 0 || a->head_dim % 8) return fail(FD_ERR_INVALID_ARG, "head_dim %d must be a positive multiple of 8", a->head_dim);
+  if (a->head_dim > 128) return fail(FD_ERR_UNSUPPORTED, "head_dim %d > 128 has no kernel", a->head_dim);
+  if (a->page_size <= 0) return fail(FD_ERR_INVALID_ARG, "page_size %d must be positive", a->page_size);
+  if (a->dtype != FD_F32 && a->dtype != FD_BF16) return fail(FD_ERR_INVALID_ARG, "unknown dtype %d", a->dtype);
+  if (!(a->sm_scale >= 0.f) || isinf(a->sm_scale)) return fail(FD_ERR_INVALID_ARG, "sm_scale must be finite and >= 0");
+  if (a->kv_chunk < 0 || a->kv_chunk % 64) return fail(FD_ERR_INVALID_ARG, "kv_chunk %d must be a non-negative multiple of 64", a->kv_chunk);
+  if (a->batch > 65535) return fail(FD_ERR_UNSUPPORTED, "batch %d > 65535", a->batch);
+  if (a->max_kv_len > (1 << 30)) return fail(FD_ERR_UNSUPPORTED, "max_kv_len %d too large", a->max_kv_len);
+
+  const int G = a->num_q_heads / a->num_kv_heads;
+  plan->use_mfma = a->dtype == FD_BF16 && a->head_dim == 128 && a->page_size % 16 == 0 &&
+                   !(a->flags & FD_ATTN_FORCE_GENERIC);
+  const int tile_rows = plan->use_mfma ? 128 : 16;
+  long long rows = (long long)a->max_new_rows * G;
+  plan->row_tiles = (int)((rows + tile_rows - 1) / tile_rows);
+  if (plan->row_tiles < 1) plan->row_tiles = 1;
+  if ((long long)plan->row_tiles * a->num_kv_heads > 65535)
+    return fail(FD_ERR_UNSUPPORTED, "max_new_rows * heads too large for one launch");
+
+  int chunk = a->kv_chunk;
+  if (chunk == 0) {
+    // enough (sequence, head, chunk) work-groups to cover 256 CUs x 2 several times over,
+    // but never chunks so short that the split partials rival the KV traffic
+    long long pairs = (long long)(a->batch > 0 ? a->batch : 1) * a->num_kv_heads * plan->row_tiles;
+    long long want = (2048 + pairs - 1) / pairs;
+    if (want < 1) want = 1;
+    long long c = ((long long)a->max_kv_len + want - 1) / want;
+    c = (c + 63) / 64 * 64;
+    long long floor_c = 256;
+    if (c < floor_c) c = floor_c;
+    chunk = (int)c;
+  }
+  plan->chunk = chunk;
+  long long mc = ((long long)a->max_kv_len + chunk - 1) / chunk;
+  if (mc < 1) mc = 1;
+  if (mc > 65535) return fail(FD_ERR_UNSUPPORTED, "kv_chunk %d gives %lld chunks (> 65535)", chunk, mc);
+  plan->max_chunks = (int)mc;
+  size_t slots = (size_t)plan->max_chunks * (size_t)(a->total_rows > 0 ? a->total_rows : 1) * a->num_q_heads;
+  plan->acc_bytes = (slots * a->head_dim * sizeof(float) + 255) / 256 * 256;
+  plan->ml_bytes = (slots * 2 * sizeof(float) + 255) / 256 * 256;
+  plan->total_bytes = plan->acc_bytes + plan->ml_bytes;
+  return FD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fd_last_error(void) { return g_err; }
+const char* fd_version(void) { return "flexdraft-gfx950 0.1"; }
+
+size_t fd_verify_draft_attn_workspace(const fd_attn_args* a) {
+  AttnPlan plan;
+  if (plan_attn(a, &plan) != FD_OK) return 0;
+  return plan.total_bytes;
+}
+
+fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
+  AttnPlan plan;
+  fd_status st = plan_attn(a, &plan);
+  if (st != FD_OK) return st;
+  g_err[0] = 0;
+  if (a->batch == 0 || a->total_rows == 0) return FD_OK;          // nothing to compute
+  if (!a->page_indptr || !a->kv_len || !a->row_indptr || !a->verify_len || !a->q || !a->k_new || !a->v_new || !a->out)
+    return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (a->max_kv_len > 0 && (!a->k_cache || !a->v_cache || !a->page_indices || a->num_pages == 0))
+    return fail(FD_ERR_INVALID_ARG, "max_kv_len > 0 needs k_cache, v_cache, page_indices and num_pages > 0");
+  if (a->max_new_rows == 0) return fail(FD_ERR_INVALID_ARG, "total_rows > 0 but max_new_rows == 0");
+  if (a->cache_stride_page < 0 || a->cache_stride_head < 0 || a->cache_stride_token < a->head_dim ||
+      a->cache_stride_page % 8 || a->cache_stride_head % 8 || a->cache_stride_token % 8)
+    return fail(FD_ERR_INVALID_ARG, "cache strides must be non-negative multiples of 8 elements, token stride >= head_dim");
+  if (!a->workspace) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
+  if (a->workspace_bytes < plan.total_bytes)
+    return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", a->workspace_bytes, plan.total_bytes);
+  if (reinterpret_cast<uintptr_t>(a->workspace) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  if (!aligned16(a->q) || !aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->out) ||
+      !aligned16(a->k_cache) || !aligned16(a->v_cache))
+    return fail(FD_ERR_INVALID_ARG, "q, k_new, v_new, out, k_cache and v_cache must be 16-byte aligned");
+
+  fd::AttnParams p;
+  p.B = a->batch; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads; p.D = a->head_dim;
+  p.G = p.Hq / p.Hkv; p.page_size = a->page_size;
+  p.total_rows = a->total_rows; p.max_kv_len = a->max_kv_len; p.max_new_rows = a->max_new_rows;
+  p.num_pages = a->num_pages; p.chunk = plan.chunk; p.max_chunks = plan.max_chunks; p.row_tiles = plan.row_tiles;
+  p.sm_scale = a->sm_scale > 0.f ? a->sm_scale : 1.0f / sqrtf((float)a->head_dim);
+  p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+  p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
+  p.page_indptr = a->page_indptr; p.page_indices = a->page_indices; p.kv_len = a->kv_len;
+  p.row_indptr = a->row_indptr; p.verify_len = a->verify_len; p.mask_vis = a->mask_vis;
+  p.q = a->q; p.k_new = a->k_new; p.v_new = a->v_new; p.out = a->out; p.lse = a->lse;
+  p.part_acc = reinterpret_cast<float*>(a->workspace);
+  p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a->workspace) + plan.acc_bytes);
+  p.status = a->status;
+
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const bool prof = g_prof_events && g_prof_used < g_prof_cap;
+  if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
+    return fail(FD_ERR_HIP, "hipEventRecord failed");
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, stream) : fd::run_attn_generic(p, a->dtype, stream);
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
+  if (prof) {
+    if (hipEventRecord(g_prof_events[2 * g_prof_used + 1], stream) != hipSuccess)
+      return fail(FD_ERR_HIP, "hipEventRecord failed");
+    ++g_prof_used;
+  }
+  e = fd::run_attn_combine(p, a->dtype, plan.use_mfma ? 1 : 0, stream);
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
+  return FD_OK;
+}
+
+size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling) {
+  return fd::accept_workspace_bytes(batch, total_rows, vocab, sampling);
+}
+
+static fd_status check_accept_common(const void* logits, fd_dtype dt, int64_t row_stride, int32_t vocab,
+                                     const int32_t* row_indptr, const int32_t* toks, int32_t batch,
+                                     int32_t total_rows, int32_t max_rows, const int32_t* accept_len,
+                                     const int32_t* bonus, const void* ws, size_t ws_bytes, int sampling) {
+  if (batch < 0 || total_rows < 0 || max_rows < 0) return fail(FD_ERR_INVALID_ARG, "negative size");
+  if (vocab <= 0) return fail(FD_ERR_INVALID_ARG, "vocab %d must be positive", vocab);
+  if (row_stride < vocab) return fail(FD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
+  if (dt != FD_F32 && dt != FD_BF16) return fail(FD_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  if (batch > 0 && (!row_indptr || !accept_len || !bonus)) return fail(FD_ERR_INVALID_ARG, "row_indptr / outputs NULL");
+  if (total_rows > 0 && (!logits || !toks)) return fail(FD_ERR_INVALID_ARG, "logits / input_tokens NULL");
+  if (total_rows > 65535) return fail(FD_ERR_UNSUPPORTED, "total_rows %d > 65535", total_rows);
+  if (batch > 0 && total_rows > 0 && max_rows == 0) return fail(FD_ERR_INVALID_ARG, "total_rows > 0 but max_rows_per_seq == 0");
+  size_t need = fd::accept_workspace_bytes(batch, total_rows, vocab, sampling);
+  if (batch > 0) {
+    if (!ws) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
+    if (ws_bytes < need) return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  }
+  return FD_OK;
+}
+
+fd_status fd_accept_greedy(const void* target_logits, fd_dtype dt, int64_t row_stride, int32_t vocab,
+                           const int32_t* row_indptr, const int32_t* input_tokens,
+                           int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                           int32_t* accept_len, int32_t* bonus_token, int32_t* row_argmax,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  fd_status st = check_accept_common(target_logits, dt, row_stride, vocab, row_indptr, input_tokens, batch,
+                                     total_rows, max_rows_per_seq, accept_len, bonus_token, workspace,
+                                     workspace_bytes, 0);
+  if (st != FD_OK) return st;
+  g_err[0] = 0;
+  if (batch == 0) return FD_OK;
+  hipError_t e = fd::run_accept_greedy(target_logits, dt, row_stride, vocab, row_indptr, input_tokens, batch,
+                                       total_rows, max_rows_per_seq, accept_len, bonus_token, row_argmax,
+                                       workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "greedy acceptance launch: %s", hipGetErrorString(e));
+  return FD_OK;
+}
+
+fd_status fd_accept_sample(const void* target_logits, const void* draft_logits, fd_dtype dt,
+                           int64_t row_stride, int32_t vocab, float temperature,
+                           const int32_t* row_indptr, const int32_t* input_tokens,
+                           const float* u_accept, const float* u_resample,
+                           int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                           int32_t* accept_len, int32_t* bonus_token,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  fd_status st = check_accept_common(target_logits, dt, row_stride, vocab, row_indptr, input_tokens, batch,
+                                     total_rows, max_rows_per_seq, accept_len, bonus_token, workspace,
+                                     workspace_bytes, 1);
+  if (st != FD_OK) return st;
+  if (!(temperature > 0.f) || isinf(temperature)) return fail(FD_ERR_INVALID_ARG, "temperature must be finite and > 0");
+  if (total_rows > 0 && (!draft_logits || !u_accept || !u_resample))
+    return fail(FD_ERR_INVALID_ARG, "draft_logits / uniforms NULL");
+  g_err[0] = 0;
+  if (batch == 0) return FD_OK;
+  hipError_t e = fd::run_accept_sample(target_logits, draft_logits, dt, row_stride, vocab, temperature, row_indptr,
+                                       input_tokens, u_accept, u_resample, batch, total_rows, max_rows_per_seq,
+                                       accept_len, bonus_token, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "sampling acceptance launch: %s", hipGetErrorString(e));
+  return FD_OK;
+}
+
+fd_status fd_profile_begin(int32_t max_calls) {
+  if (g_prof_events) return fail(FD_ERR_INVALID_ARG, "profiling already on");
+  if (max_calls <= 0 || max_calls > (1 << 20)) return fail(FD_ERR_INVALID_ARG, "max_calls out of range");
+  g_prof_events = new hipEvent_t[2 * (size_t)max_calls];
+  for (int i = 0; i < 2 * max_calls; ++i)
+    if (hipEventCreate(&g_prof_events[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof_events[j]);
+      delete[] g_prof_events; g_prof_events = nullptr;
+      return fail(FD_ERR_HIP, "hipEventCreate failed");
+    }
+  g_prof_cap = max_calls; g_prof_used = 0;
+  return FD_OK;
+}
+
+int32_t fd_profile_end(float* ms_out, int32_t capacity) {
+  if (!g_prof_events) return 0;
+  int n = 0;
+  for (int i = 0; i < g_prof_used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_prof_events[2 * i + 1]) == hipSuccess &&
+        hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) == hipSuccess) {
+      if (ms_out && n < capacity) ms_out[n++] = ms;
+    }
+  }
+  for (int i = 0; i < 2 * g_prof_cap; ++i) (void)hipEventDestroy(g_prof_events[i]);
+  delete[] g_prof_events; g_prof_events = nullptr; g_prof_cap = g_prof_used = 0;
+  return n;
+}
+
+fd_status fd_stream_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst) return fail(FD_ERR_INVALID_ARG, "src / dst NULL");
+  if (bytes % 16 || !aligned16(src) || !aligned16(dst)) return fail(FD_ERR_INVALID_ARG, "copy must be 16-byte aligned and sized");
+  g_err[0] = 0;
+  if (bytes == 0) return FD_OK;
+  hipError_t e = fd::run_stream_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "copy launch: %s", hipGetErrorString(e));
+  return FD_OK;
+}
+
+}  // extern "C"

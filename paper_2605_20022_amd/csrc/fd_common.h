@@ -1,0 +1,114 @@
+// Shared device/host helpers of the gfx950 library (internal; not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "flexdraft.h"
+
+#define FD_WAVE 64
+
+namespace fd {
+
+typedef unsigned short bf16_t;                                   // raw bf16 bit pattern
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16-byte vector
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((unsigned)b) << 16); }
+
+// round-to-nearest-even; inputs here are finite
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+__device__ __forceinline__ void flag_status(uint32_t* status, uint32_t bit) {
+  if (status) atomicOr(status, bit);
+}
+
+// Per-sequence description every attention kernel derives from the device arrays,
+// clamped to the host-declared bounds so that no later access leaves the buffers.
+struct SeqInfo {
+  int L;        // cached prefix tokens
+  int row0;     // first packed row
+  int n;        // new rows
+  int k;        // verify rows
+  int v;        // verify rows visible to the mask block
+  int page0;    // first entry in page_indices
+  int npages;   // entries available
+};
+
+struct AttnParams {
+  int B, Hq, Hkv, D, G, page_size;
+  int total_rows, max_kv_len, max_new_rows, num_pages;
+  int chunk;          // cached tokens per work-group
+  int max_chunks;     // grid extent over chunks
+  int row_tiles;      // grid extent over row tiles
+  float sm_scale;
+  const void* k_cache; const void* v_cache;
+  long long sp, sh, st;                       // cache strides in elements
+  const int* page_indptr; const int* page_indices; const int* kv_len;
+  const int* row_indptr; const int* verify_len; const int* mask_vis;
+  const void* q; const void* k_new; const void* v_new;
+  void* out; float* lse;
+  float* part_acc;    // [max_chunks][R][Hq][D]
+  float* part_ml;     // [max_chunks][R][Hq][2]
+  uint32_t* status;
+};
+
+__device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) {
+  SeqInfo s;
+  int L = p.kv_len[i];
+  int r0 = p.row_indptr[i], r1 = p.row_indptr[i + 1];
+  int k = p.verify_len[i];
+  int pg0 = p.page_indptr[i], pg1 = p.page_indptr[i + 1];
+  uint32_t bad = 0;
+  if (L < 0 || L > p.max_kv_len) bad |= FD_DEV_KV_LEN_RANGE;
+  s.L = clampi(L, 0, p.max_kv_len);
+  if (r0 < 0 || r0 > p.total_rows || r1 < r0 || r1 > p.total_rows || r1 - r0 > p.max_new_rows) bad |= FD_DEV_ROWS_RANGE;
+  s.row0 = clampi(r0, 0, p.total_rows);
+  s.n = clampi(r1 - r0, 0, p.max_new_rows);
+  if (s.row0 + s.n > p.total_rows) s.n = p.total_rows - s.row0;
+  if (k < 0 || k > s.n) bad |= FD_DEV_ROWS_RANGE;
+  s.k = clampi(k, 0, s.n);
+  int v = s.k;
+  if (p.mask_vis) {
+    v = p.mask_vis[i];
+    if (v < 0 || v > s.k) bad |= FD_DEV_ROWS_RANGE;
+    v = clampi(v, 0, s.k);
+  }
+  s.v = v;
+  s.page0 = pg0 < 0 ? 0 : pg0;
+  s.npages = pg1 - pg0 < 0 ? 0 : pg1 - pg0;
+  int need = (s.L + p.page_size - 1) / p.page_size;
+  if (pg0 < 0 || need > s.npages) {       // page list shorter than kv_len claims
+    bad |= FD_DEV_PAGE_RANGE;
+    s.L = s.npages * p.page_size < s.L ? s.npages * p.page_size : s.L;
+  }
+  if (bad) flag_status(p.status, bad);
+  return s;
+}
+
+// May new row `r` (0-based within the sequence) look at new row `t`?  Sec. 4.1 mask rules.
+__device__ __forceinline__ bool new_key_visible(int r, int t, int n, int k, int v) {
+  if (t >= n) return false;
+  return r < k ? (t <= r) : (t < v || t >= k);
+}
+
+}  // namespace fd

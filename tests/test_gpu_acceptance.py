@@ -1,0 +1,153 @@
+"""GPU parity: fd_accept_greedy / fd_accept_sample (through the C ABI) against the oracle.
+
+Greedy results are integers and must match bit for bit, ties included (lowest index).
+Sampling decisions are compared exactly wherever the oracle's decision margin is above
+what fp32 exponentials can resolve (gpu_harness.ACCEPT_MARGIN / RESAMPLE_MARGIN); a
+thin-margin decision may land on the adjacent outcome, which is verified to be adjacent.
+"""
+import numpy as np
+import pytest
+
+from oracle import acceptance as oc
+from paper_2605_20022_amd import workloads as W
+from tests.gpu_harness import compare_sampling, run_greedy, run_sample
+
+pytestmark = pytest.mark.gpu
+
+
+def _greedy_case(fd, logits, indptr, toks, **kw):
+    acc, bon, am = run_greedy(fd, logits, indptr, toks, **kw)
+    V = kw.get("vocab")
+    ref_logits = logits if V is None else logits[:, :V]
+    o_acc, o_bon, o_am = oc.accept_greedy(ref_logits, indptr, toks)
+    assert np.array_equal(am, o_am), "row arg-max differs"
+    assert np.array_equal(acc, o_acc) and np.array_equal(bon, o_bon)
+    return o_acc, o_bon, o_am
+
+
+def test_cfg1_greedy_fp32_vocab_1000(fd):
+    """4 verify rows; drafts 1 and 2 equal the target arg-max, draft 3 is random."""
+    _, a = W.CONFIGS["cfg1"]
+    lg = W.make_logits(a, 4)["target_logits"]
+    _, _, am = oc.accept_greedy(lg, [0, 4], [0, 0, 0, 0])
+    rng = np.random.default_rng(a.seed)
+    toks = np.array([5, am[0], am[1], (am[2] + 1 + rng.integers(0, 998)) % 1000], dtype=np.int32)
+    o_acc, o_bon, _ = _greedy_case(fd, lg, [0, 4], toks)
+    assert o_acc[0] == 2 and o_bon[0] == am[2]           # committed length 3
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_greedy_ties_ragged_and_edges(fd, dtype):
+    rng = np.random.default_rng(3)
+    for V in (1, 7, 513, 4099, 20000):
+        ks = [0, 1, 3, 70, 2, 0, 5]
+        indptr = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+        Rv = int(indptr[-1])
+        # coarse grid of values => many exact ties, including at the maximum; some -inf
+        vals = rng.integers(-4, 5, size=(Rv, V)).astype(np.float32) * 0.5
+        vals[rng.random((Rv, V)) < 0.05] = -np.inf
+        vals[3] = -np.inf; vals[3, V - 1] = -1.0       # maximum in the very last slot
+        vals[4] = 2.0                                   # whole row tied: index 0 wins
+        logits = W.f32_to_bf16_bits(vals) if dtype == "bf16" else vals
+        _, _, am = oc.accept_greedy(logits, indptr, np.zeros(Rv, dtype=np.int64))
+        toks = rng.integers(0, V, size=Rv)
+        agree = rng.random(Rv) < 0.8
+        toks[1:][agree[:-1]] = am[:-1][agree[:-1]]
+        _greedy_case(fd, logits, indptr, toks.astype(np.int32))
+
+
+def test_greedy_row_stride_and_unaligned_rows(fd):
+    """vocab smaller than the row pitch, and an odd pitch that breaks 16-byte row alignment."""
+    rng = np.random.default_rng(8)
+    vals = rng.standard_normal((6, 1003)).astype(np.float32)
+    logits = W.f32_to_bf16_bits(vals)
+    toks = rng.integers(0, 990, size=6).astype(np.int32)
+    _greedy_case(fd, logits, [0, 2, 6], toks, vocab=990)
+    _greedy_case(fd, vals, [0, 2, 6], toks, vocab=1001)
+
+
+def test_cfg3_greedy_vocab_151936(fd):
+    w, a = W.CONFIGS["cfg3"]
+    lens = W.make_lengths(w)
+    indptr = W.verify_row_indptr(lens)
+    lg = W.make_logits(a, int(indptr[-1]))["target_logits"]
+    _, _, am = oc.accept_greedy(lg, indptr, np.zeros(int(indptr[-1]), dtype=np.int64))
+    toks = W.make_draft_tokens_agreeing(a, indptr, am)
+    o_acc, _, _ = _greedy_case(fd, lg, indptr, toks)
+    # the workload really exercises the tie-break and a spread of accepted lengths
+    f = (lg.astype(np.uint32) << 16).view(np.float32)
+    ties = int(((f == f.max(axis=1, keepdims=True)).sum(axis=1) > 1).sum())
+    assert ties >= 1 and len(set(o_acc.tolist())) >= 3
+
+
+def _sampling_inputs(a, indptr, T):
+    Rv = int(indptr[-1])
+    lg = W.make_logits(a, Rv)
+
+    def q_row(j):
+        return oc.softmax64(oc.to_f64(lg["draft_logits"][j]) / T)
+    toks = W.make_draft_tokens_from_probs(a, indptr, q_row)
+    return lg, toks
+
+
+def _sample_case(fd, a, indptr, T):
+    lg, toks = _sampling_inputs(a, indptr, T)
+    acc, bon = run_sample(fd, lg["target_logits"], lg["draft_logits"], indptr, toks, lg["u_accept"], lg["u_resample"], T)
+    o_acc, o_bon, info = oc.accept_sample(lg["target_logits"], lg["draft_logits"], indptr, toks,
+                                          lg["u_accept"], lg["u_resample"], T)
+    thin = compare_sampling(acc, bon, o_acc, o_bon, info, indptr, lg["target_logits"], lg["draft_logits"], toks,
+                            lg["u_accept"], lg["u_resample"], T)
+    return o_acc, thin
+
+
+@pytest.mark.parametrize("dtype,V,T", [("f32", 50, 1.0), ("bf16", 1000, 0.7), ("bf16", 5003, 1.0), ("f32", 20011, 1.3)])
+def test_sampling_small_vocabularies(fd, dtype, V, T):
+    a = W.AcceptWorkload("s", dtype, V, "sample", 2.0, draft_noise_std=0.7, temperature=T, seed=77 + V)
+    ks = [3, 0, 1, 9, 17, 2]
+    indptr = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+    o_acc, thin = _sample_case(fd, a, indptr, T)
+    assert thin <= 1
+
+
+def test_sampling_degenerate_distributions(fd):
+    """p == q: everything is kept.  Drafter one-hot on a token the target gives zero mass: rejected at once."""
+    V = 300
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((4, V)).astype(np.float32)
+    toks = rng.integers(0, V, size=4).astype(np.int32)
+    ua = np.full(4, 0.999, dtype=np.float32); ur = rng.random(4).astype(np.float32)
+    acc, bon = run_sample(fd, x, x.copy(), [0, 4], toks, ua, ur, 1.0)
+    o_acc, o_bon, _ = oc.accept_sample(x, x, [0, 4], toks, ua, ur, 1.0)
+    assert acc[0] == 3 == o_acc[0] and bon[0] == o_bon[0]
+    xt = x.copy(); xd = np.full((4, V), -np.inf, dtype=np.float32)
+    xt[0, 17] = -np.inf; xd[:, 17] = 0.0
+    toks2 = np.array([0, 17, 17, 17], dtype=np.int32)
+    acc, bon = run_sample(fd, xt, xd, [0, 4], toks2, np.zeros(4, dtype=np.float32), ur, 1.0)
+    o_acc, o_bon, _ = oc.accept_sample(xt, xd, [0, 4], toks2, np.zeros(4), ur, 1.0)
+    assert acc[0] == 0 == o_acc[0] and bon[0] == o_bon[0] and bon[0] != 17
+
+
+def test_cfg5_sampling_vocab_151936(fd):
+    w, a = W.CONFIGS["cfg5"]
+    lens = W.make_lengths(w)
+    indptr = W.verify_row_indptr(lens)
+    o_acc, thin = _sample_case(fd, a, indptr, a.temperature)
+    assert thin <= 1
+    assert o_acc.min() >= 0 and o_acc.max() <= 15
+
+
+def test_acceptance_argument_errors(fd):
+    import torch
+    lg = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+    ip = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    tk = torch.zeros(2, dtype=torch.int32, device="cuda")
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda"); bon = torch.zeros(1, dtype=torch.int32, device="cuda")
+    small = fd.alloc_workspace(0)[:16]
+    with pytest.raises(fd.FlexDraftError) as e:
+        fd.fd_accept_greedy(lg, ip, tk, acc, bon, max_rows_per_seq=2, workspace=small)
+    assert e.value.code in (1, 3)
+    ws = fd.alloc_workspace(fd.fd_accept_workspace(1, 2, 64, True))
+    u = torch.zeros(2, dtype=torch.float32, device="cuda")
+    with pytest.raises(fd.FlexDraftError) as e:
+        fd.fd_accept_sample(lg, lg, ip, tk, u, u, acc, bon, temperature=0.0, max_rows_per_seq=2, workspace=ws)
+    assert e.value.code == 1

@@ -1,0 +1,201 @@
+"""GPU parity: fd_verify_draft_attn (through the C ABI) against the fp64 oracle.
+
+Tolerances (stated by the build's target): fp32 path 1e-5 absolute; bf16 path 2e-2
+absolute on N(0,1)-scaled inputs, tightened here to 2e-2 of the largest reference
+magnitude when outputs are small (gpu_harness.assert_attn_close).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_20022_amd import workloads as W
+from tests.gpu_harness import AttnCall, assert_attn_close, oracle_attention, subset_inputs
+
+pytestmark = pytest.mark.gpu
+
+FORCE_GENERIC = 1
+
+
+def _wl(name, dtype, B, Hq, Hkv, D, ps, kv, kr, m, std=1.0, seed=1, shuffled=True):
+    return W.AttnWorkload(name, dtype, B, Hq, Hkv, D, ps, kv, kr, m, std, shuffled_pages=shuffled,
+                          spare_page_frac=0.1, seed=seed)
+
+
+def _check(fd, inp, dtype, what, mask_vis=None, lse_tol=None, **kw):
+    call = AttnCall(fd, inp, mask_vis=mask_vis, **kw)
+    out, lse = call.run()
+    ref, ref_lse = oracle_attention(inp, mask_vis)
+    err = assert_attn_close(out, ref, dtype, what)
+    if lse is not None:
+        tol = lse_tol if lse_tol is not None else (1e-5 if dtype == "f32" else 2e-2)
+        assert np.abs(lse - ref_lse).max() <= tol, f"{what}: lse diff {np.abs(lse - ref_lse).max():.3e}"
+    return err
+
+
+def test_cfg1_tiny_fp32(fd):
+    w, _ = W.CONFIGS["cfg1"]
+    inp = W.make_attention_inputs(w)
+    _check(fd, inp, "f32", "cfg1")
+    for v in (0, 2):
+        _check(fd, inp, "f32", f"cfg1 mask_vis={v}", mask_vis=[v])
+
+
+@pytest.mark.parametrize("case", [
+    # (B, Hq, Hkv, D, page, kv range, k range, m)
+    dict(B=3, Hq=4, Hkv=2, D=64, ps=16, kv=(1, 200), kr=(1, 5), m=3),
+    dict(B=2, Hq=8, Hkv=1, D=128, ps=8, kv=(30, 90), kr=(0, 3), m=4),       # k may be 0: mask-only rows
+    dict(B=4, Hq=6, Hkv=3, D=32, ps=1, kv=(0, 40), kr=(1, 4), m=0),         # page size 1, empty prefixes
+    dict(B=2, Hq=2, Hkv=2, D=128, ps=32, kv=(100, 300), kr=(2, 20), m=9),   # > 16 tile rows: several row tiles
+])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_generic_kernel_small_cases(fd, case, dtype):
+    w = _wl("small", dtype, case["B"], case["Hq"], case["Hkv"], case["D"], case["ps"], case["kv"], case["kr"],
+            case["m"], seed=11)
+    inp = W.make_attention_inputs(w)
+    rng = np.random.default_rng(5)
+    mv = np.array([rng.integers(0, k + 1) for k in inp["verify_len"]], dtype=np.int32)
+    for chunk in (0, 64):
+        _check(fd, inp, dtype, f"generic {case} chunk={chunk}", flags=FORCE_GENERIC, kv_chunk=chunk)
+        _check(fd, inp, dtype, f"generic {case} chunk={chunk} mask_vis", mask_vis=mv, flags=FORCE_GENERIC, kv_chunk=chunk)
+
+
+@pytest.mark.parametrize("case", [
+    dict(B=3, G=4, Hkv=2, ps=16, kv=(1, 500), kr=(1, 8), m=8),
+    dict(B=2, G=4, Hkv=1, ps=16, kv=(64, 64), kr=(4, 4), m=4),             # exactly one full tile
+    dict(B=4, G=1, Hkv=3, ps=32, kv=(0, 300), kr=(0, 6), m=5),             # G=1, empty prefixes, k=0
+    dict(B=2, G=8, Hkv=1, ps=64, kv=(100, 700), kr=(16, 16), m=16),        # 256 tile rows: two row tiles
+    dict(B=3, G=2, Hkv=2, ps=16, kv=(200, 900), kr=(1, 40), m=40),         # > 64 new rows: two new-row tiles
+    dict(B=5, G=4, Hkv=2, ps=16, kv=(1, 130), kr=(1, 16), m=0),            # sequential mode, ragged k
+])
+def test_mfma_kernel_small_cases(fd, case):
+    w = _wl("small", "bf16", case["B"], case["G"] * case["Hkv"], case["Hkv"], 128, case["ps"], case["kv"],
+            case["kr"], case["m"], seed=21)
+    inp = W.make_attention_inputs(w)
+    rng = np.random.default_rng(6)
+    mv = np.array([rng.integers(0, k + 1) for k in inp["verify_len"]], dtype=np.int32)
+    for chunk in (0, 64, 192):
+        _check(fd, inp, "bf16", f"mfma {case} chunk={chunk}", kv_chunk=chunk)
+    _check(fd, inp, "bf16", f"mfma {case} mask_vis", mask_vis=mv, kv_chunk=128)
+    # the two kernels are independent implementations: they must also agree with each other
+    a, _ = AttnCall(fd, inp, kv_chunk=128).run()
+    b, _ = AttnCall(fd, inp, kv_chunk=128, flags=FORCE_GENERIC).run()
+    assert np.abs(a - b).max() <= 2e-2
+
+
+def test_mfma_strided_cache_layout(fd):
+    """Token-major cache ([page][slot][head][D]) addressed through the stride arguments."""
+    w = _wl("nhd", "bf16", 3, 8, 2, 128, 16, (10, 400), (2, 6), 6, seed=31)
+    inp = W.make_attention_inputs(w)
+    ref, _ = oracle_attention(inp)
+    call = AttnCall(fd, inp)
+    for name in ("k_cache", "v_cache"):
+        nhd = call.d[name].permute(0, 2, 1, 3).contiguous()      # [P, ps, Hkv, D] storage
+        call.d[name] = nhd.permute(0, 2, 1, 3)                   # logical [P, Hkv, ps, D] view
+    a = call.args
+    a.k_cache = call.d["k_cache"].data_ptr(); a.v_cache = call.d["v_cache"].data_ptr()
+    a.cache_stride_page, a.cache_stride_head, a.cache_stride_token = (call.d["k_cache"].stride(i) for i in range(3))
+    out, _ = call.run()
+    assert_attn_close(out, ref, "bf16", "strided cache")
+
+
+def test_mask_semantics_on_gpu(fd):
+    """Properties of Sec. 4.1 checked on the device result itself: verify rows do not move when
+    mask-token Q/K/V change; the (k, m) call restricted to verify rows equals the (k, 0) call."""
+    w = _wl("sem", "bf16", 2, 8, 2, 128, 16, (100, 260), (5, 5), 7, seed=41)
+    inp = W.make_attention_inputs(w)
+    base, _ = AttnCall(fd, inp).run()
+    is_verify = np.zeros(inp["q"].shape[0], dtype=bool)
+    for i in range(2):
+        is_verify[inp["row_indptr"][i]:inp["row_indptr"][i] + inp["verify_len"][i]] = True
+    pert = dict(inp)
+    rng = np.random.default_rng(0)
+    for name in ("q", "k_new", "v_new"):
+        x = inp[name].copy()
+        x[~is_verify] = W.f32_to_bf16_bits(rng.standard_normal(x[~is_verify].shape).astype(np.float32) * 3)
+        pert[name] = x
+    moved, _ = AttnCall(fd, pert).run()
+    assert np.array_equal(base[is_verify], moved[is_verify])
+    assert not np.array_equal(base[~is_verify], moved[~is_verify])
+    seq = dict(inp)
+    for name in ("q", "k_new", "v_new"):
+        seq[name] = inp[name][is_verify]
+    seq["row_indptr"] = np.concatenate([[0], np.cumsum(inp["verify_len"])]).astype(np.int32)
+    only_verify, _ = AttnCall(fd, seq).run()
+    assert np.array_equal(only_verify, base[is_verify])
+
+
+def test_cfg2_contiguous_parallel_mode(fd):
+    w, _ = W.CONFIGS["cfg2"]
+    inp = W.make_attention_inputs(w)
+    _check(fd, inp, "bf16", "cfg2")
+    sharp = W.make_attention_inputs(w, std=1.0)          # N(0,1) twin: outputs of order 0.1 - 1
+    _check(fd, sharp, "bf16", "cfg2 sharp")
+
+
+def test_cfg3_ragged_paged_batch(fd):
+    w, _ = W.CONFIGS["cfg3"]
+    inp = W.make_attention_inputs(w)
+    _check(fd, inp, "bf16", "cfg3")
+    sharp = W.make_attention_inputs(w, std=1.0)
+    _check(fd, sharp, "bf16", "cfg3 sharp")
+
+
+def test_cfg4_large_batch_sequential_sampled(fd):
+    """Full-size launch; the oracle recomputes a sample of the sequences one by one
+    (shortest, longest, and a few seeded picks), the rest is checked for finiteness."""
+    w, _ = W.CONFIGS["cfg4"]
+    inp = W.make_attention_inputs(w)
+    out, lse = AttnCall(fd, inp).run()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    rng = np.random.default_rng(4)
+    picks = {int(np.argmin(inp["kv_len"])), int(np.argmax(inp["kv_len"])),
+             int(np.argmin(inp["verify_len"])), int(np.argmax(inp["verify_len"]))}
+    picks |= set(int(x) for x in rng.choice(w.batch, size=4, replace=False))
+    sub = subset_inputs(inp, sorted(picks))
+    ref, ref_lse = oracle_attention(sub)
+    assert_attn_close(out[sub["_rows"]], ref, "bf16", "cfg4 sample")
+    assert np.abs(lse[sub["_rows"]] - ref_lse).max() <= 2e-2
+
+
+def test_cfg5_long_context(fd):
+    w, _ = W.CONFIGS["cfg5"]
+    inp = W.make_attention_inputs(w)
+    out, lse = AttnCall(fd, inp).run()
+    ref, ref_lse = oracle_attention(inp)
+    assert_attn_close(out, ref, "bf16", "cfg5")
+    assert np.abs(lse - ref_lse).max() <= 2e-2
+    sharp = W.make_attention_inputs(w.scaled(batch=1), std=1.0)
+    _check(fd, sharp, "bf16", "cfg5 sharp (one sequence)")
+
+
+def test_argument_errors_and_device_status(fd):
+    w = _wl("err", "bf16", 2, 8, 2, 128, 16, (50, 80), (2, 2), 2, seed=51)
+    inp = W.make_attention_inputs(w)
+    call = AttnCall(fd, inp)
+    # workspace too small
+    call.args.workspace_bytes = 16
+    with pytest.raises(fd.FlexDraftError) as e:
+        fd.fd_verify_draft_attn(call.args)
+    assert e.value.code == 3
+    call.args.workspace_bytes = call.workspace.numel()
+    # bad head ratio
+    call.args.num_kv_heads = 3
+    with pytest.raises(fd.FlexDraftError) as e:
+        fd.fd_verify_draft_attn(call.args)
+    assert e.value.code == 1
+    call.args.num_kv_heads = 2
+    # kv_len above the declared bound is clamped and reported through the status word, no fault
+    call.args.max_kv_len = 32
+    fd.fd_verify_draft_attn(call.args)
+    torch.cuda.synchronize()
+    assert int(call.status.item()) & 1
+    # a page id outside the pool is reported too
+    call2 = AttnCall(fd, inp)
+    call2.d["page_indices"][0] = 10 ** 6
+    fd.fd_verify_draft_attn(call2.args)
+    torch.cuda.synchronize()
+    assert int(call2.status.item()) & 4
+    # empty batch is a no-op
+    empty = AttnCall(fd, subset_inputs(inp, []))
+    fd.fd_verify_draft_attn(empty.args)
+    torch.cuda.synchronize()

@@ -1,0 +1,83 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and its pure-host entry points (workspace queries, argument validation)
+behave.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_20022_amd import flexdraft as fd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flexdraft.h")).read()
+    return re.findall(r"FD_API\s+[\w\s\*]+?\b(fd_\w+)\s*\(", text)
+
+
+def test_header_symbols_are_exported():
+    lib = fd.load()
+    names = _declared_symbols()
+    assert len(names) >= 10 and set(names) == set(fd.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in flexdraft.h but not exported"
+    assert fd.fd_version().startswith("flexdraft-gfx950")
+
+
+def test_struct_layout_matches_header():
+    """The ctypes mirror must have the size the C compiler gives the struct (checked via a
+    tiny C program compiled on the spot with the host compiler)."""
+    import subprocess, tempfile
+    src = '#include <stdio.h>\n#include "flexdraft.h"\nint main(){printf("%zu %zu %zu\\n", sizeof(fd_attn_args), ' \
+          '__builtin_offsetof(fd_attn_args, k_cache), __builtin_offsetof(fd_attn_args, status));return 0;}\n'
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.c"), "w").write(src)
+        subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), os.path.join(d, "t.c"), "-o", os.path.join(d, "t")])
+        size, off_k, off_s = map(int, subprocess.check_output([os.path.join(d, "t")]).split())
+    assert size == C.sizeof(fd.fd_attn_args)
+    assert off_k == fd.fd_attn_args.k_cache.offset and off_s == fd.fd_attn_args.status.offset
+
+
+def _args(**kw):
+    a = fd.fd_attn_args()
+    a.batch = 4; a.num_q_heads = 32; a.num_kv_heads = 8; a.head_dim = 128; a.page_size = 16
+    a.dtype = fd.FD_BF16; a.total_rows = 128; a.max_kv_len = 32768; a.max_new_rows = 32; a.num_pages = 9000
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_attention_workspace_query_and_validation():
+    a = _args()
+    need = fd.fd_verify_draft_attn_workspace(a)
+    # chunks * rows * heads * (D + 2) floats, chunk count decided by the library
+    per_chunk = 128 * 32 * (128 + 2) * 4
+    assert need >= per_chunk and need % 256 == 0 and (need // per_chunk) <= 64
+    # explicit chunk size fixes the count
+    a.kv_chunk = 4096
+    assert fd.fd_verify_draft_attn_workspace(a) == 8 * per_chunk
+    assert fd.fd_verify_draft_attn_workspace(_args(num_kv_heads=5)) == 0
+    assert fd.fd_verify_draft_attn_workspace(_args(head_dim=100)) == 0
+    assert fd.fd_verify_draft_attn_workspace(_args(kv_chunk=100)) == 0
+    for bad, code in ((dict(num_kv_heads=5), 1), (dict(head_dim=256), 2), (dict(page_size=0), 1), (dict(dtype=7), 1)):
+        with pytest.raises(fd.FlexDraftError) as e:
+            fd._check(fd.load().fd_verify_draft_attn(C.byref(_args(**bad)), None))
+        assert e.value.code == code
+    # missing pointers are rejected before anything is launched
+    with pytest.raises(fd.FlexDraftError) as e:
+        fd._check(fd.load().fd_verify_draft_attn(C.byref(_args()), None))
+    assert e.value.code == 1 and "NULL" in str(e.value)
+
+
+def test_accept_workspace_query_and_validation():
+    g = fd.fd_accept_workspace(16, 128, 151936, False)
+    s = fd.fd_accept_workspace(4, 64, 151936, True)
+    assert g > 0 and s > g and g % 256 == 0 and s % 256 == 0
+    assert fd.fd_accept_workspace(1, 1, 0, False) == 0
+    lib = fd.load()
+    rc = lib.fd_accept_greedy(None, fd.FD_BF16, 10, 20, None, None, 1, 1, 1, None, None, None, None, 0, None)
+    assert rc == 1 and b"row_stride" in lib.fd_last_error()
+    rc = lib.fd_accept_sample(None, None, fd.FD_BF16, 20, 20, 1.0, None, None, None, None, 0, 0, 0, None, None, None, 0, None)
+    assert rc == 0      # empty batch: nothing to do
