@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify+draft hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is
+already resident in HBM: fd_verify_draft_attn (streaming kernel + split combine) followed
+by the workload's acceptance call (greedy or sampling) when it has one.  The KV pool and
+the logits are rotated over enough device copies that no step finds its input in the
+256 MB last-level cache.  One JSON line is printed; `value` is algorithmic KV-cache bytes
+per step divided by the step time.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+COLD_FOOTPRINT = 1.25e9         # bytes of distinct copies a rotating input must span
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Step:
+    """Device state of one workload: rotating KV pools / logits and the prepared C-ABI arguments."""
+
+    def __init__(self, fd, name, torch):
+        from paper_2605_20022_amd import workloads as W
+        from tests.gpu_harness import AttnCall, to_dev
+        self.fd, self.torch, self.name = fd, torch, name
+        w, a = W.CONFIGS[name]
+        self.w, self.a = w, a
+        t0 = time.time()
+        inp = W.make_attention_inputs(w)
+        self.inp = inp
+        self.kv_bytes = W.kv_bytes(w, inp["kv_len"])
+        self.flops = W.attention_flops(w, inp["kv_len"], inp["row_indptr"])
+        call = AttnCall(fd, inp, want_lse=False)
+        self.call = call
+        pool_bytes = call.d["k_cache"].numel() * call.d["k_cache"].element_size() * 2
+        n_pools = int(min(64, max(1, np.ceil(COLD_FOOTPRINT / pool_bytes))))
+        self.pools = [(call.d["k_cache"], call.d["v_cache"])]
+        for _ in range(n_pools - 1):
+            self.pools.append((call.d["k_cache"].clone(), call.d["v_cache"].clone()))
+        self.attn_args = []
+        for k, v in self.pools:
+            args = fd.fd_attn_args.from_buffer_copy(call.args)
+            args.k_cache = k.data_ptr(); args.v_cache = v.data_ptr()
+            self.attn_args.append(args)
+        # acceptance inputs
+        self.acc = None
+        if a is not None:
+            indptr = W.verify_row_indptr(inp)
+            Rv = int(indptr[-1])
+            lg = W.make_logits(a, Rv)
+            if a.mode == "greedy":
+                f = (lg["target_logits"].astype(np.uint32) << 16).view(np.float32) if a.dtype == "bf16" else lg["target_logits"]
+                agree = np.argmax(f, axis=1)          # input synthesis only: what the stand-in drafter agrees with
+                toks = W.make_draft_tokens_agreeing(a, indptr, agree)
+            else:
+                d32 = (lg["draft_logits"].astype(np.uint32) << 16).view(np.float32) if a.dtype == "bf16" else lg["draft_logits"]
+
+                def q_row(j):                          # input synthesis only: the stand-in drafter's distribution
+                    x = d32[j].astype(np.float64) / a.temperature
+                    e = np.exp(x - x.max())
+                    return e / e.sum()
+                toks = W.make_draft_tokens_from_probs(a, indptr, q_row)
+            B = w.batch
+            d = dict(indptr=torch.from_numpy(indptr).cuda(), toks=torch.from_numpy(toks).cuda(),
+                     acc=torch.zeros(B, dtype=torch.int32, device="cuda"),
+                     bon=torch.zeros(B, dtype=torch.int32, device="cuda"),
+                     kmax=int(np.diff(indptr).max()), Rv=Rv)
+            tg = to_dev(lg["target_logits"])
+            per_copy = tg.numel() * tg.element_size() * (2 if a.mode == "sample" else 1)
+            n_cp = int(min(64, max(1, np.ceil(COLD_FOOTPRINT / per_copy))))
+            d["target"] = [tg] + [tg.clone() for _ in range(n_cp - 1)]
+            if a.mode == "sample":
+                dr = to_dev(lg["draft_logits"])
+                d["draft"] = [dr] + [dr.clone() for _ in range(n_cp - 1)]
+                d["ua"] = torch.from_numpy(lg["u_accept"]).cuda(); d["ur"] = torch.from_numpy(lg["u_resample"]).cuda()
+            d["ws"] = fd.alloc_workspace(fd.fd_accept_workspace(B, Rv, a.vocab, a.mode == "sample"))
+            d["logit_bytes"] = per_copy
+            self.acc = d
+        self.i = 0
+        log(f"[{name}] inputs ready in {time.time() - t0:.1f}s: KV {self.kv_bytes / 1e6:.1f} MB x {n_pools} pools, "
+            f"rows {inp['q'].shape[0]}, acceptance {a.mode if a else 'none'}")
+
+    def attn(self):
+        self.fd.fd_verify_draft_attn(self.attn_args[self.i % len(self.attn_args)])
+
+    def accept(self):
+        d, a = self.acc, self.a
+        j = self.i % len(d["target"])
+        if a.mode == "greedy":
+            self.fd.fd_accept_greedy(d["target"][j], d["indptr"], d["toks"], d["acc"], d["bon"],
+                                     max_rows_per_seq=d["kmax"], workspace=d["ws"])
+        else:
+            self.fd.fd_accept_sample(d["target"][j], d["draft"][j], d["indptr"], d["toks"], d["ua"], d["ur"],
+                                     d["acc"], d["bon"], temperature=a.temperature, max_rows_per_seq=d["kmax"],
+                                     workspace=d["ws"])
+
+    def step(self):
+        self.attn()
+        if self.acc is not None:
+            self.accept()
+        self.i += 1
+
+    def timed(self, steps, warmup, profile_kernel=False):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        if profile_kernel:
+            self.fd.fd_profile_begin(steps)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        kern_ms = self.fd.fd_profile_end(steps) if profile_kernel else []
+        return dt / steps * 1e3, kern_ms
+
+    def timed_parts(self, steps, warmup):
+        """Event-bracketed time of the attention call alone and the acceptance call alone."""
+        torch = self.torch
+        res = {}
+        for label, fn in (("attn", self.attn), ("accept", self.accept if self.acc is not None else None)):
+            if fn is None:
+                continue
+            for _ in range(warmup):
+                fn(); self.i += 1
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for s, e in evs:
+                s.record(); fn(); e.record(); self.i += 1
+            torch.cuda.synchronize()
+            ts = sorted(s.elapsed_time(e) for s, e in evs)
+            res[label] = dict(median_ms=ts[len(ts) // 2], min_ms=ts[0])
+        return res
+
+
+def cpu_baseline(name, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole sequences are
+    added (shortest first would bias; seeded order is used) until about budget_s of CPU time."""
+    from paper_2605_20022_amd import workloads as W
+    from tests.gpu_harness import oracle_attention, subset_inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    w, _ = W.CONFIGS[name]
+    inp = W.make_attention_inputs(w)
+    order = np.random.default_rng(0).permutation(w.batch)
+    done_bytes, spent, used = 0, 0.0, 0
+    for i in order:
+        sub = subset_inputs(inp, [int(i)])
+        t0 = time.perf_counter()
+        oracle_attention(sub)
+        spent += time.perf_counter() - t0
+        done_bytes += W.kv_bytes(w, sub["kv_len"]); used += 1
+        if spent > budget_s:
+            break
+    return dict(value=done_bytes / spent / 1e9, unit="GB/s", cores=int(threads), kind="oracle",
+                sample=f"{used} of {w.batch} sequences of {name} (oracle attention only), {spent:.1f} s")
+
+
+def read_traffic(name):
+    """HBM bytes per launch of the streaming kernel from the committed counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"attn_mfma_{name}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--all-configs", action="store_true", help="also report every configuration in per_config")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(sequences, KV heads or KV ranges would shard it; see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_20022_amd import flexdraft as fd
+    fd.load()                                  # raises if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    st = Step(fd, args.workload, torch)
+    ms_per_step, kern_ms = st.timed(args.steps, args.warmup, profile_kernel=True)
+    parts = st.timed_parts(min(args.steps, 100), 5)
+    kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else None
+    value = st.kv_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = st.kv_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_avg_ms else None
+    out = {
+        "metric": "verify+draft attn: KV GB/s & % HBM peak; acceptance seqs/s at vocab 151936",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": st.w.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={st.w.batch}, KV len {st.w.kv_len_range}, page {st.w.page_size}, "
+                               f"{st.w.num_q_heads}/{st.w.num_kv_heads} heads, D={st.w.head_dim}, "
+                               f"k in {st.w.verify_len_range} + m={st.w.mask_len}, acceptance "
+                               f"{st.a.mode + ' V=' + str(st.a.vocab) if st.a else 'none'}",
+                   "kv_bytes_per_step": st.kv_bytes, "attention_flops_per_step": st.flops,
+                   "kv_pools_rotated": len(st.pools)},
+        "pct_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "attn_ms": parts.get("attn"), "accept_ms": parts.get("accept"),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2) if achieved else None, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4) if achieved else None,
+                     "traffic": read_traffic(args.workload), "kernel": "attn_mfma_kernel",
+                     "kernel_avg_ms": round(kern_avg_ms, 5) if kern_avg_ms else None,
+                     "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2) if kern_avg_ms else None},
+    }
+    if "accept" in parts:
+        out["accept_seqs_per_s"] = round(st.w.batch / (parts["accept"]["median_ms"] * 1e-3), 1)
+        out["accept_logits_GBps"] = round(st.acc["logit_bytes"] / (parts["accept"]["median_ms"] * 1e-3) / 1e9, 1)
+    del st
+    torch.cuda.empty_cache()
+
+    if args.all_configs:
+        per = {}
+        for name in ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"]:
+            s2 = Step(fd, name, torch)
+            n = 50
+            _, km = s2.timed(n, 5, profile_kernel=True)
+            p2 = s2.timed_parts(n, 3)
+            k_ms = float(np.mean(km))
+            per[name] = {"kv_MB": round(s2.kv_bytes / 1e6, 2), "kernel_us": round(k_ms * 1e3, 2),
+                         "kernel_kv_GBps": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9, 1),
+                         "kernel_frac_hbm_peak": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "attn_call_us": round(p2["attn"]["median_ms"] * 1e3, 2),
+                         "mfma_tflops": round(s2.flops / (k_ms * 1e-3) / 1e12, 2)}
+            if "accept" in p2:
+                per[name]["accept_us"] = round(p2["accept"]["median_ms"] * 1e3, 2)
+                per[name]["accept_seqs_per_s"] = round(s2.w.batch / (p2["accept"]["median_ms"] * 1e-3), 1)
+            del s2
+            torch.cuda.empty_cache()
+        out["per_config"] = per
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

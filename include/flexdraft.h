@@ -99,7 +99,7 @@ typedef struct fd_attn_args {
   int32_t num_q_heads;        /* Hq, multiple of num_kv_heads                                 */
   int32_t num_kv_heads;       /* Hkv                                                          */
   int32_t head_dim;           /* D: multiple of 8, <= 128 (MFMA kernel: 128)                  */
-  int32_t page_size;          /* tokens per page, >= 1 (MFMA kernel: multiple of 16)          */
+  int32_t page_size;          /* tokens per page, >= 1 (MFMA kernel: power of two >= 16)      */
   int32_t dtype;              /* fd_dtype                                                     */
   float   sm_scale;           /* 0 => 1/sqrt(head_dim)                                        */
   int32_t flags;              /* FD_ATTN_*                                                    */
@@ -108,7 +108,7 @@ typedef struct fd_attn_args {
   int32_t max_kv_len;         /* >= every kv_len[i]                                           */
   int32_t max_new_rows;       /* >= every n_i                                                 */
   int32_t num_pages;          /* physical pages in the pool; page ids are checked against it  */
-  int32_t kv_chunk;           /* cached tokens per work-group, multiple of 64; 0 => automatic */
+  int32_t kv_chunk;           /* cached tokens per work-group, multiple of 128; 0 => automatic */
   int32_t reserved;
   const void *k_cache;        /* device                                                       */
   const void *v_cache;        /* device                                                       */

@@ -4,12 +4,19 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 namespace fd {
 hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
-hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, hipStream_t st);
-hipError_t run_attn_mfma(const AttnParams& p, hipStream_t st);
+hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int skip_single, hipStream_t st);
+bool attn_mfma_supports(int dtype, int head_dim, int page_size);
+int attn_mfma_tile_keys();
+int attn_mfma_rows_per_wg(int max_tile_rows);
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, bool* needs_combine, hipStream_t st);
+hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st);
+int attn_mfma_num_wgs();
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, int batch, int hkv, int rt_max, size_t* off_ml, size_t* off_meta);
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab, int sampling);
 hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,
                              const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
@@ -62,10 +69,11 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
   if (a->max_kv_len > (1 << 30)) return fail(FD_ERR_UNSUPPORTED, "max_kv_len %d too large", a->max_kv_len);
 
   const int G = a->num_q_heads / a->num_kv_heads;
-  plan->use_mfma = a->dtype == FD_BF16 && a->head_dim == 128 && a->page_size % 16 == 0 &&
-                   !(a->flags & FD_ATTN_FORCE_GENERIC);
-  const int tile_rows = plan->use_mfma ? 128 : 16;
+  plan->use_mfma = fd::attn_mfma_supports(a->dtype, a->head_dim, a->page_size) && !(a->flags & FD_ATTN_FORCE_GENERIC);
+  const int tile_keys = plan->use_mfma ? fd::attn_mfma_tile_keys() : 64;
+  if (a->kv_chunk % tile_keys) return fail(FD_ERR_INVALID_ARG, "kv_chunk %d must be a multiple of %d for this kernel", a->kv_chunk, tile_keys);
   long long rows = (long long)a->max_new_rows * G;
+  const int tile_rows = plan->use_mfma ? fd::attn_mfma_rows_per_wg((int)(rows > 128 ? 128 : rows)) : 16;
   plan->row_tiles = (int)((rows + tile_rows - 1) / tile_rows);
   if (plan->row_tiles < 1) plan->row_tiles = 1;
   if ((long long)plan->row_tiles * a->num_kv_heads > 65535)
@@ -79,8 +87,8 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
     long long want = (2048 + pairs - 1) / pairs;
     if (want < 1) want = 1;
     long long c = ((long long)a->max_kv_len + want - 1) / want;
-    c = (c + 63) / 64 * 64;
-    long long floor_c = 256;
+    c = (c + tile_keys - 1) / tile_keys * tile_keys;
+    long long floor_c = 512;
     if (c < floor_c) c = floor_c;
     chunk = (int)c;
   }
@@ -89,6 +97,14 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
   if (mc < 1) mc = 1;
   if (mc > 65535) return fail(FD_ERR_UNSUPPORTED, "kv_chunk %d gives %lld chunks (> 65535)", chunk, mc);
   plan->max_chunks = (int)mc;
+  if (plan->use_mfma) {
+    // persistent kernel: partial storage depends on the launch size only, not on the lengths
+    plan->max_chunks = 1;
+    plan->acc_bytes = plan->ml_bytes = 0;
+    plan->total_bytes = fd::attn_mfma_workspace(fd::attn_mfma_num_wgs(), tile_rows, a->batch, a->num_kv_heads,
+                                                plan->row_tiles, nullptr, nullptr);
+    return FD_OK;
+  }
   size_t slots = (size_t)plan->max_chunks * (size_t)(a->total_rows > 0 ? a->total_rows : 1) * a->num_q_heads;
   plan->acc_bytes = (slots * a->head_dim * sizeof(float) + 255) / 256 * 256;
   plan->ml_bytes = (slots * 2 * sizeof(float) + 255) / 256 * 256;
@@ -145,19 +161,25 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   p.part_acc = reinterpret_cast<float*>(a->workspace);
   p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a->workspace) + plan.acc_bytes);
   p.status = a->status;
+#ifdef FD_TIMELINE
+  p.tl = reinterpret_cast<unsigned long long*>(strtoull(getenv("FD_TL_PTR") ? getenv("FD_TL_PTR") : "0", nullptr, 16));
+#endif
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const bool prof = g_prof_events && g_prof_used < g_prof_cap;
   if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
     return fail(FD_ERR_HIP, "hipEventRecord failed");
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, stream) : fd::run_attn_generic(p, a->dtype, stream);
+  bool mfma_combine = false;
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, (a->flags >> 8) & 3, &mfma_combine, stream)
+                               : fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
   if (prof) {
     if (hipEventRecord(g_prof_events[2 * g_prof_used + 1], stream) != hipSuccess)
       return fail(FD_ERR_HIP, "hipEventRecord failed");
     ++g_prof_used;
   }
-  e = fd::run_attn_combine(p, a->dtype, plan.use_mfma ? 1 : 0, stream);
+  e = plan.use_mfma ? fd::run_attn_mfma_combine(p, a->workspace, stream)
+                    : fd::run_attn_combine(p, a->dtype, 0, 0, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
   return FD_OK;
 }

@@ -24,7 +24,9 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
   __shared__ float Vs[GEN_KEYS][GEN_DMAX];
   __shared__ float Ps[GEN_ROWS][GEN_KEYS + 1];
 
-  const int chunk_id = blockIdx.x;
+  // Consecutive work-group ids go to different XCDs; rotating the chunk index by head and
+  // sequence keeps any one XCD from collecting only the long (or only the short) chunks.
+  const int chunk_id = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x;
   const int g = blockIdx.y % p.Hkv, rt = blockIdx.y / p.Hkv;
   const int seq = blockIdx.z;
   const SeqInfo s = load_seq(p, seq);
@@ -138,13 +140,15 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
 // Combine the per-chunk partials of every (row, head):
 //   M = max_c m_c;  out = sum_c e^{m_c - M} acc_c / sum_c e^{m_c - M} l_c;  lse = M + log(sum)
 // `log2_units` says the partial maxima are in base-2 exponent units (the MFMA kernel) or
-// natural units (the scalar kernel).  grid (ceil(Hq*D/256), max_new_rows, B).
+// natural units (the scalar kernel).  `skip_single`: sequences that fit one chunk were already
+// normalised and stored by the streaming kernel.  grid (ceil(Hq*D/256), max_new_rows, B).
 // ---------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p, int log2_units) {
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p, int log2_units, int skip_single) {
   const int seq = blockIdx.z, nn = blockIdx.y;
   const SeqInfo s = load_seq(p, seq);
   if (nn >= s.n) return;
+  if (skip_single && s.L <= p.chunk) return;     // the streaming kernel already wrote these rows
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= p.Hq * p.D) return;
   const int hq = idx / p.D, d = idx % p.D;
@@ -176,10 +180,10 @@ hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, hipStream_t st) {
+hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int skip_single, hipStream_t st) {
   dim3 grid((p.Hq * p.D + 255) / 256, p.max_new_rows, p.B);
-  if (dtype == FD_BF16) hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, grid, dim3(256), 0, st, p, log2_units);
-  else hipLaunchKernelGGL(attn_combine_kernel<float>, grid, dim3(256), 0, st, p, log2_units);
+  if (dtype == FD_BF16) hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, grid, dim3(256), 0, st, p, log2_units, skip_single);
+  else hipLaunchKernelGGL(attn_combine_kernel<float>, grid, dim3(256), 0, st, p, log2_units, skip_single);
   return hipGetLastError();
 }
 

@@ -1,39 +1,69 @@
 // Hybrid-mask verify+draft attention (Sec. 4.1), bf16 MFMA kernel for gfx950, head_dim 128.
 //
-// One work-group of four waves owns one (sequence, KV head, KV chunk, 128-tile-row block)
-// and streams the chunk's keys and values 64 tokens at a time:
+// Work decomposition.  An *item* is one (sequence, KV head, block of up to ROWS_WG tile
+// rows); a tile row is (new row, query head of the group), so K and V are read from HBM once
+// for all rows and all G heads of the KV head.  An item consists of ceil(L/64) tiles of 64
+// cached keys followed by the tile(s) of the sequence's own new rows.  All tiles of all
+// items, in (sequence, head, row block) order, form one line of work that is cut into equal
+// shares, one per persistent work-group (two work-groups per CU), so that every CU streams
+// the same number of bytes whatever the length mix of the batch.  A work-group that owns a
+// whole item normalises and stores it; an item cut by a share boundary leaves one split
+// partial (base-2 running max, sum, un-normalised O) per work-group that touched it, merged
+// by the combine kernel below.
 //
-//   global --16-byte coalesced loads, one page slab per instruction--> registers
-//          --> LDS (double buffered, one barrier per tile)
+// Streaming of one tile by the four waves of a work-group:
+//   global --16-byte coalesced loads, one 4 KB page slab per instruction--> registers
+//          (the next tile is in flight while the current one is multiplied)
+//          --> LDS, double buffered, K rows padded to 272 B, V rows to 288 B, one barrier/tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS (ds_read_b128),
-//                      B = Q fragments held in registers for the whole kernel
+//                      B = Q fragments held in registers for the whole item
 //   online softmax     in the accumulator layout: a lane owns ONE query row (column of
 //                      S^T) and 16 of each 32 keys, so the row maximum needs one exchange
 //                      with lane^32 and the row sum none until the end
 //   O^T += V^T P^T     A = V^T fragments fetched with ds_read_b64_tr_b16 (the LDS transpose
 //                      read of gfx950), B = P packed to bf16 straight from the S^T registers
 //
-// A tile row is (new row, query head of the group); wave w owns tile rows 32w..32w+31, so
-// K and V are read from HBM once for all rows and all G heads of the KV head.  The cached
-// prefix is unmasked (every new row sees all of it); only the ragged last tile and the
-// tile of new rows apply the visibility rule, in registers.  Each work-group leaves split
-// partials (base-2 running max, sum, un-normalised O) for the combine kernel.
+// The tile rows in use form RB = 1, 2 or 4 blocks of 32; wave w takes row block w % RB and,
+// of each tile's two 32-key blocks, the one with index w / RB (both when RB = 4).  With few
+// rows the waves split the keys, with many rows they split the rows; waves that shared a row
+// block merge their running (max, sum, O) through LDS at the end of the piece.
+//
+// The cached prefix is unmasked (every new row sees all of it, Sec. 4.1); only the ragged
+// last tile and the tile of new rows apply the visibility rule, in registers.
 #include "fd_common.h"
+#include <type_traits>
 
 namespace fd {
 
 constexpr int MF_BLOCK = 256;
 constexpr int MF_TK = 64;                 // keys per LDS tile
 constexpr int MF_D = 128;
-constexpr int MF_ROWS = 128;              // tile rows per work-group
-constexpr int MF_KSTR = MF_D + 8;         // LDS row pitch in bf16 elements (272 bytes)
-constexpr int MF_VSTR = MF_D + 8;
-constexpr int MF_TILE_ELEMS = MF_TK * MF_KSTR;
-constexpr size_t MF_LDS_BYTES = (size_t)2 * 2 * MF_TILE_ELEMS * sizeof(bf16_t);   // K,V x 2 buffers
+constexpr int MF_KSTR = MF_D + 8;         // K row pitch in bf16 elements (272 bytes)
+constexpr int MF_VSTR = MF_D + 16;        // V row pitch (288 bytes): best for the transpose reads
+constexpr int MF_K_ELEMS = MF_TK * MF_KSTR;
+constexpr int MF_V_ELEMS = MF_TK * MF_VSTR;
+constexpr int MF_BUF_ELEMS = MF_K_ELEMS + MF_V_ELEMS;     // one K+V tile
+constexpr size_t MF_LDS_BYTES = (size_t)2 * MF_BUF_ELEMS * sizeof(bf16_t);   // double buffered
+constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
+constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-struct TileRegs { u32x4 k[4]; u32x4 v[4]; };
+struct TileRegs { u32x4 k[MF_GROUPS]; u32x4 v[MF_GROUPS]; };
+
+// Launch-time scheduling parameters and the split-partial storage.
+struct MfmaSched {
+  int page_shift;
+  int num_wgs;        // persistent work-groups launched
+  int min_share;      // automatic shares are never smaller than this many tiles
+  int fixed_share;    // > 0: tiles per work-group asked for by the caller
+  int rt_max;         // row blocks per (sequence, head) the meta arrays are laid out for
+  float* part_acc;    // [2 * num_wgs][ROWS_WG][D]
+  float* part_ml;     // [2 * num_wgs][ROWS_WG][2]
+  int* meta_first;    // [B][Hkv][rt_max]: slot of the item's first piece
+  int* meta_last;     // [B][Hkv][rt_max]: work-group that processed the item's last tile
+};
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
@@ -45,243 +75,573 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
-__global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
-  bf16_t* Ks = lds;                             // [2][MF_TK][MF_KSTR]
-  bf16_t* Vs = lds + 2 * MF_TILE_ELEMS;         // [2][MF_TK][MF_VSTR]
+// Branch-free form of the Sec. 4.1 rule for new row r looking at new row t.
+__device__ __forceinline__ bool new_vis(int r, int t, int n, int k, int v) {
+  const bool verify_row = r < k;
+  const bool a = t <= r;
+  const bool b = (t < v) | (t >= k);
+  return (t < n) & (verify_row ? a : b);
+}
 
-  const int chunk_id = blockIdx.x;
-  const int g = blockIdx.y % p.Hkv, rt = blockIdx.y / p.Hkv;
-  const int seq = blockIdx.z;
-  const SeqInfo s = load_seq(p, seq);
-  const int nchunks = max(1, (s.L + p.chunk - 1) / p.chunk);
-  const int rows_total = s.n * p.G;
-  if (chunk_id >= nchunks || rt * MF_ROWS >= rows_total) return;
+// Tiles of one item of this sequence, and how many items (heads x row blocks) it has.
+__device__ __forceinline__ void seq_shape(const AttnParams& p, const SeqInfo& s, int rows_wg, int& tiles, int& items) {
+  if (s.n <= 0) { tiles = 0; items = 0; return; }
+  tiles = (s.L + MF_TK - 1) / MF_TK + (s.n + MF_TK - 1) / MF_TK;
+  items = p.Hkv * ((s.n * p.G + rows_wg - 1) / rows_wg);
+}
+
+// A 64-bit value known to be equal in every lane, moved to scalar registers.
+__device__ __forceinline__ long long uniform_ll(long long v) {
+  unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(v & 0xffffffffll));
+  unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)v >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
+__device__ __forceinline__ long long wave_incl_scan(long long v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) { long long o = __shfl_up(v, off); if (lane >= off) v += o; }
+  return v;
+}
+
+// DBG (measurement builds only): 1 = stream tiles but skip the arithmetic, 2 = do the arithmetic on
+// whatever the first tile left in LDS and skip the global loads; both produce meaningless output.
+// MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
+template <int DBG, int MAXRB>
+__global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
+  constexpr int ROWS_WG = 32 * MAXRB;
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+  __shared__ long long sh_ll[MF_BLOCK / 64];
+  __shared__ int sh_found[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
+  const int w = blockIdx.x;
   const bf16_t* Kc = reinterpret_cast<const bf16_t*>(p.k_cache);
   const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
   const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
   const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
 
-  // ---- this lane's query row -----------------------------------------------------------
-  const int T_row = rt * MF_ROWS + wave * 32 + c32;
-  const bool row_valid = T_row < rows_total;
-  const bool wave_active = (rt * MF_ROWS + wave * 32) < rows_total;
-  const int nn = T_row / p.G;                                   // new-row index within the sequence
-  const int hq = g * p.G + T_row % p.G;
-  bf16x8 qf[8];
+  // ---- total work, this work-group's share ------------------------------------------------
+  long long part = 0;
+  for (int i = tid; i < p.B; i += MF_BLOCK) {
+    SeqInfo s = load_seq_t<false>(p, i);
+    int T, I; seq_shape(p, s, ROWS_WG, T, I);
+    part += (long long)T * I;
+  }
+  part = wave_incl_scan(part, lane);
+  if (lane == 63) sh_ll[wave] = part;
+  __syncthreads();
+  long long total = 0;
+  for (int q = 0; q < MF_BLOCK / 64; ++q) total += sh_ll[q];
+  total = uniform_ll(total);
+  __syncthreads();
+  if (total <= 0) return;
+  long long want = sc_.fixed_share > 0 ? sc_.fixed_share : max((long long)sc_.min_share, (total + sc_.num_wgs - 1) / sc_.num_wgs);
+  long long weff_ll = (total + want - 1) / want;
+  const int W_eff = (int)min((long long)sc_.num_wgs, weff_ll);
+  if (w >= W_eff) return;
+  const long long g0 = (long long)w * total / W_eff;
+  const long long g1 = (long long)(w + 1) * total / W_eff;
+  if (g1 <= g0) return;
+
+  // ---- sequence that contains tile g0: block-wide prefix scan over the batch ---------------
   {
-    const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(s.row0 + (row_valid ? nn : 0)) * p.Hq + hq) * MF_D + 8 * h;
-#pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      u32x4 w = {0u, 0u, 0u, 0u};
-      if (row_valid) w = *reinterpret_cast<const u32x4*>(qp + 16 * st);
-      qf[st] = as_bf16x8(w);
+    long long base_t = 0;
+    if (tid == 0) sh_found[0] = -1;
+    __syncthreads();
+    for (int blk = 0; blk < p.B; blk += MF_BLOCK) {
+      const int i = blk + tid;
+      int T = 0, I = 0;
+      if (i < p.B) { SeqInfo s = load_seq_t<false>(p, i); seq_shape(p, s, ROWS_WG, T, I); }
+      const long long vt = (long long)T * I;
+      long long it = wave_incl_scan(vt, lane);
+      if (lane == 63) sh_ll[wave] = it;
+      __syncthreads();
+      long long wt = 0, bt = 0;
+      for (int q = 0; q < MF_BLOCK / 64; ++q) {
+        if (q < wave) wt += sh_ll[q];
+        bt += sh_ll[q];
+      }
+      const long long lo = base_t + wt + it - vt, hi = base_t + wt + it;
+      if (i < p.B && lo <= g0 && g0 < hi) {
+        sh_found[0] = i; sh_found[1] = (int)(lo & 0xffffffffll); sh_found[2] = (int)(lo >> 32);
+      }
+      base_t += bt;
+      __syncthreads();
+      if (sh_found[0] >= 0) break;
     }
   }
-
-  // ---- tile schedule -------------------------------------------------------------------
-  const int c0 = chunk_id * p.chunk;
-  const int c1 = min(s.L, c0 + p.chunk);
-  const int n_ct = c1 > c0 ? (c1 - c0 + MF_TK - 1) / MF_TK : 0;
-  const int n_nt = (chunk_id == nchunks - 1) ? (s.n + MF_TK - 1) / MF_TK : 0;
-  const int NT = n_ct + n_nt;
+  int seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
+  if (seq < 0) return;                                           // cannot happen for consistent data
+  long long Pt = uniform_ll(((long long)(unsigned)sh_found[1]) | ((long long)sh_found[2] << 32));   // tiles before seq
 
   const int ld_key = tid >> 4;                 // 0..15: key within a 16-key group
   const int ld_col = (tid & 15) * 8;           // element offset of this thread's 16 bytes
-
-  // physical page of each 16-key group of a cached tile (uniform across the work-group)
-  auto fetch_pages = [&](int t, int (&pg)[4]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int gs = c0 + t * MF_TK + 16 * j;        // first key of the group
-      int ph = -1;
-      if (t < n_ct && gs < c1) {
-        ph = p.page_indices[s.page0 + gs / p.page_size];
-        if (ph < 0 || ph >= p.num_pages) { flag_status(p.status, FD_DEV_PAGE_RANGE); ph = -1; }
-      }
-      pg[j] = ph;
-    }
-  };
-
-  auto load_tile = [&](int t, const int (&pg)[4], TileRegs& r) {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    if (t < n_ct) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int gs = c0 + t * MF_TK + 16 * j;
-        int key = gs + ld_key;
-        r.k[j] = z; r.v[j] = z;
-        if (pg[j] >= 0 && key < c1) {
-          long long off = (long long)pg[j] * p.sp + (long long)g * p.sh +
-                          (long long)(gs % p.page_size + ld_key) * p.st + ld_col;
-          r.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + off));
-          r.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vc + off));
-        }
-      }
-    } else {
-      int base = (t - n_ct) * MF_TK;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int key = base + 16 * j + ld_key;
-        r.k[j] = z; r.v[j] = z;
-        if (key < s.n) {
-          long long off = ((long long)(s.row0 + key) * p.Hkv + g) * MF_D + ld_col;
-          r.k[j] = *reinterpret_cast<const u32x4*>(Kn + off);
-          r.v[j] = *reinterpret_cast<const u32x4*>(Vn + off);
-        }
-      }
-    }
-  };
-
-  auto store_tile = [&](int buf, const TileRegs& r) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int row = 16 * j + ld_key;
-      *reinterpret_cast<u32x4*>(Ks + buf * MF_TILE_ELEMS + row * MF_KSTR + ld_col) = r.k[j];
-      *reinterpret_cast<u32x4*>(Vs + buf * MF_TILE_ELEMS + row * MF_VSTR + ld_col) = r.v[j];
-    }
-  };
-
-  // ---- running softmax state: one query row per lane ------------------------------------
+  const int page_mask = p.page_size - 1;
   const float cs = p.sm_scale * 1.4426950408889634f;           // scores are kept in base-2 units
-  float m_run = -INFINITY, l_lane = 0.f;
-  f32x16 o[4];
-#pragma unroll
-  for (int b = 0; b < 4; ++b)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
-  int pg[4];
-  TileRegs regs;
-  fetch_pages(0, pg);
-  load_tile(0, pg, regs);
-  fetch_pages(1, pg);
-  store_tile(0, regs);
-  __syncthreads();
+  auto get_seq = [&](int i) {
+    SeqInfo s = load_seq(p, i);
+    s.L = __builtin_amdgcn_readfirstlane(s.L);       s.row0 = __builtin_amdgcn_readfirstlane(s.row0);
+    s.n = __builtin_amdgcn_readfirstlane(s.n);       s.k = __builtin_amdgcn_readfirstlane(s.k);
+    s.v = __builtin_amdgcn_readfirstlane(s.v);       s.page0 = __builtin_amdgcn_readfirstlane(s.page0);
+    s.npages = __builtin_amdgcn_readfirstlane(s.npages);
+    return s;
+  };
+  SeqInfo s = get_seq(seq);
+  int T, I; seq_shape(p, s, ROWS_WG, T, I);
 
-  for (int t = 0; t < NT; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < NT) {
-      load_tile(t + 1, pg, regs);
-      fetch_pages(t + 2, pg);
+  long long g = g0;
+  bool first_piece = true;
+  while (g < g1) {
+    while (g >= Pt + (long long)T * I) {       // move on to the sequence that holds tile g
+      Pt += (long long)T * I;
+      ++seq;
+      if (seq >= p.B) return;
+      s = get_seq(seq);
+      seq_shape(p, s, ROWS_WG, T, I);
+    }
+    const long long local = g - Pt;
+    const int item = (int)(local / T);
+    const int tile0 = (int)(local - (long long)item * T);
+    const int RT = I / p.Hkv;
+    const int head = item / RT, rt = item - head * RT;
+    const int nt = (int)min((long long)(T - tile0), g1 - g);   // tiles of this piece
+    const bool whole = (tile0 == 0) && (nt == T);
+    const int slot = 2 * w + (first_piece ? 0 : 1);
+    const long long meta_idx = ((long long)seq * p.Hkv + head) * sc_.rt_max + rt;
+    if (tid == 0 && rt < sc_.rt_max) {
+      if (tile0 == 0) sc_.meta_first[meta_idx] = slot;
+      if (tile0 + nt == T) sc_.meta_last[meta_idx] = w;
     }
 
-    if (wave_active) {
-      const bf16_t* Kb = Ks + buf * MF_TILE_ELEMS;
-      const bf16_t* Vb = Vs + buf * MF_TILE_ELEMS;
-      // ---- S^T = K Q^T : two 32-key blocks ----
-      f32x16 sc[2];
+    // ---- wave roles for this item ----------------------------------------------------------
+    const int rows_total = s.n * p.G;
+    const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
+    const int RB = rows_here <= 32 ? 1 : ((MAXRB == 2 || rows_here <= 64) ? 2 : 4);   // 32-row blocks in use
+    const int KQ = min(4 / RB, MF_BLOCKS);                           // waves sharing a row block
+    const int rb = wave % RB, kq = wave / RB;                        // kq >= KQ: no block, idle
+    const int trow = rb * 32 + c32;                                  // tile row within the item
+    const int T_row = rt * ROWS_WG + trow;
+    const bool row_valid = T_row < rows_total;
+    const bool wave_has_rows = rt * ROWS_WG + rb * 32 < rows_total;
+    const int nn = T_row / p.G;                                      // new-row index within the sequence
+    const int hq = head * p.G + T_row % p.G;
+    bf16x8 qf[8];
+    {
+      const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(s.row0 + (row_valid ? nn : 0)) * p.Hq + hq) * MF_D + 8 * h;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int st = 0; st < 8; ++st) {
+        u32x4 wq = {0u, 0u, 0u, 0u};
+        if (row_valid) wq = *reinterpret_cast<const u32x4*>(qp + 16 * st);
+        qf[st] = as_bf16x8(wq);
+      }
+    }
+
+    // ---- tiles of the piece: [tile0, tile0 + nt) of the item; the first n_ct_all are cached ----
+    const int n_ct_all = (s.L + MF_TK - 1) / MF_TK;
+    const int c1 = s.L;
+    const long long ld_off = (long long)head * p.sh + (long long)ld_key * p.st + ld_col;
+    const int* pi = p.page_indices + s.page0;
+
+    // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
+    // fetched with scalar loads one tile ahead and range-checked when the addresses are formed.
+    auto fetch_pages = [&](int tau, int (&pg)[MF_GROUPS]) {
+      if (tau < n_ct_all) {
+        const int base = tau * MF_TK;
+        if (base + MF_TK <= c1) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sc[kb][i] = 0.f;
-        const bf16_t* kp = Kb + (32 * kb + c32) * MF_KSTR + 8 * h;
+          for (int j = 0; j < MF_GROUPS; ++j)
+            pg[j] = sload(pi, __builtin_amdgcn_readfirstlane((base + 16 * j) >> sc_.page_shift));
+        } else {
 #pragma unroll
-        for (int st = 0; st < 8; ++st) {
-          bf16x8 kf = as_bf16x8(*reinterpret_cast<const u32x4*>(kp + 16 * st));
-          sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sc[kb], 0, 0, 0);
+          for (int j = 0; j < MF_GROUPS; ++j) {
+            int gs = base + 16 * j;
+            pg[j] = gs < c1 ? sload(pi, __builtin_amdgcn_readfirstlane(gs >> sc_.page_shift)) : 0;
+          }
         }
       }
-      // ---- visibility: ragged tail of the cache, or the new-row tile (Sec. 4.1 rules) ----
-      const bool is_new = t >= n_ct;
-      const int tile_base = is_new ? (t - n_ct) * MF_TK : c0 + t * MF_TK;
-      if (is_new || tile_base + MF_TK > c1) {
+    };
+
+    auto load_tile = [&](int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      if (tau < n_ct_all) {
+        const int base = tau * MF_TK;
+        bool bad = false;
+        if (base + MF_TK <= c1) {                // full tile: no per-key guards
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+          for (int j = 0; j < MF_GROUPS; ++j) {
+            int ph = pg[j];
+            if ((unsigned)ph >= (unsigned)p.num_pages) { bad = true; ph = 0; }
+            long long off = (long long)ph * p.sp + (long long)((base + 16 * j) & page_mask) * p.st + ld_off;
+            r.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + off));
+            r.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vc + off));
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < MF_GROUPS; ++j) {
+            int gs = base + 16 * j;
+            int ph = pg[j];
+            if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < c1); ph = 0; }
+            r.k[j] = z; r.v[j] = z;
+            if (gs + ld_key < c1) {
+              long long off = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + ld_off;
+              r.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + off));
+              r.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vc + off));
+            }
+          }
+        }
+        if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
+      } else {
+        const int base = (tau - n_ct_all) * MF_TK;
+#pragma unroll
+        for (int j = 0; j < MF_GROUPS; ++j) {
+          int key = base + 16 * j + ld_key;
+          r.k[j] = z; r.v[j] = z;
+          if (key < s.n) {
+            long long off = ((long long)(s.row0 + key) * p.Hkv + head) * MF_D + ld_col;
+            r.k[j] = *reinterpret_cast<const u32x4*>(Kn + off);
+            r.v[j] = *reinterpret_cast<const u32x4*>(Vn + off);
+          }
+        }
+      }
+    };
+
+    auto store_tile = [&](int buf, const TileRegs& r) {
+      bf16_t* Kb = lds + buf * MF_BUF_ELEMS;
+      bf16_t* Vb = Kb + MF_K_ELEMS;
+#pragma unroll
+      for (int j = 0; j < MF_GROUPS; ++j) {
+        int row = 16 * j + ld_key;
+        *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[j];
+        *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[j];
+      }
+    };
+
+    // ---- running softmax state: one query row per lane ------------------------------------
+    float m_run = -INFINITY, l_lane = 0.f;
+    f32x16 o[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
+
+    int pg[MF_GROUPS];
+#pragma unroll
+    for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
+    TileRegs regs;
+    fetch_pages(tile0, pg);
+    load_tile(tile0, pg, regs);
+    fetch_pages(tile0 + 1, pg);
+    store_tile(0, regs);
+    __syncthreads();
+
+    for (int t = 0; t < nt; ++t) {
+      const int tau = tile0 + t;
+      const bf16_t* Ks = lds + (t & 1) * MF_BUF_ELEMS;
+      const bf16_t* Vs = Ks + MF_K_ELEMS;
+      if (t + 1 < nt && DBG != 2) {
+        load_tile(tau + 1, pg, regs);
+        fetch_pages(tau + 2, pg);
+      }
+
+      // valid keys in this tile and whether the visibility rule has to be evaluated
+      const bool is_new = tau >= n_ct_all;
+      const int tile_base = is_new ? (tau - n_ct_all) * MF_TK : tau * MF_TK;
+      const int tile_end = is_new ? s.n : c1;                     // keys at or beyond are invisible
+      const bool masked = is_new | (tile_base + MF_TK > tile_end);
+
+      if (DBG != 1 && wave_has_rows && kq < KQ) {
+        // S^T = K Q^T for the 32 keys of block kb
+        auto compute_S = [&](int kb) -> f32x16 {
+          f32x16 sc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+          const bf16_t* kp = Ks + (32 * kb + c32) * MF_KSTR + 8 * h;
+#pragma unroll
+          for (int st = 0; st < 8; ++st) {
+            bf16x8 kf = as_bf16x8(*reinterpret_cast<const u32x4*>(kp + 16 * st));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sc, 0, 0, 0);
+          }
+          return sc;
+        };
+        // visibility + online softmax (base 2) of one block; returns P^T as packed bf16 pairs
+        auto softmax_block = [&](f32x16 sc, int kb, unsigned (&pk)[8]) {
+          if (masked) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              int key = tile_base + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+              bool vis = is_new ? new_vis(nn, key, s.n, s.k, s.v) : (key < c1);
+              sc[i] = vis ? sc[i] : -INFINITY;
+            }
+          }
+          float mx = fmaxf(sc[0], sc[1]);
+#pragma unroll
+          for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sc[i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run, mx * cs);
+          const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;  // row with nothing visible yet
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_sub);
+          m_run = m_new;
+          if (__any(alpha != 1.f)) {
+            l_lane *= alpha;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+          }
+          float pr[16];
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            int key = tile_base + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-            bool vis = is_new ? new_key_visible(nn, key, s.n, s.k, s.v) : (key < c1);
-            if (!vis) sc[kb][i] = -INFINITY;
+            pr[i] = __builtin_amdgcn_exp2f(fmaf(sc[i], cs, -m_sub));
+            l_lane += pr[i];
           }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) pk[i] = pack_bf16x2(pr[2 * i], pr[2 * i + 1]);
+        };
+        // O^T += V^T P^T for block kb
+        auto compute_PV = [&](int kb, const unsigned (&pk)[8]) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            u32x4 pw = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+            const bf16x8 pf = as_bf16x8(pw);
+            // keys of this k-step for lane-half h: base+4h+{0..3} and base+8+4h+{0..3}
+            const bf16_t* vp = Vs + (32 * kb + 16 * j + 4 * h + (l16 >> 2)) * MF_VSTR + 16 * (c32 >> 4) + 4 * (l16 & 3);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+              s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b));
+              s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b + 8 * MF_VSTR));
+              s16x8 vv = {v1[0], v1[1], v1[2], v1[3], v2[0], v2[1], v2[2], v2[3]};
+              o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o[b], 0, 0, 0);
+            }
+          }
+        };
+        auto run_blocks = [&](auto nblk_c, int stride) {
+          constexpr int NBLK = decltype(nblk_c)::value;
+#pragma unroll
+          for (int ib = 0; ib < NBLK; ++ib) {
+            const int kb = kq + ib * stride;
+            if (tile_base + 32 * kb >= tile_end) break;            // block entirely past the end
+            f32x16 sc = compute_S(kb);
+            unsigned pk[8];
+            softmax_block(sc, kb, pk);
+            compute_PV(kb, pk);
+          }
+        };
+        if (tile_base + 32 * kq < tile_end) {
+          if (MAXRB == 4 && RB == 4) run_blocks(std::integral_constant<int, MF_BLOCKS>{}, 1);   // all blocks of the tile
+          else run_blocks(std::integral_constant<int, 1>{}, 0);                                // block kq only
+        }
       }
-      // ---- online softmax (base 2) ----
-      float mx = sc[0][0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sc[0][i]);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[1][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * cs);
-      const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;   // row with nothing visible yet
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_sub);
-      m_run = m_new;
-      if (__any(alpha != 1.f)) {
-        l_lane *= alpha;
+
+      if (t + 1 < nt && DBG != 2) store_tile((t + 1) & 1, regs);
+      __syncthreads();                           // tile t fully consumed, tile t+1 visible
+    }
+
+    // ---- merge the waves that shared a row block (through LDS, same register layout) ------
+    float* xch = reinterpret_cast<float*>(lds);                    // [wave][66][64] floats
+    if (KQ > 1) {
+      if (kq > 0 && kq < KQ) {
+        float* dst = xch + (size_t)wave * 66 * 64 + lane;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+          for (int i = 0; i < 16; ++i) dst[(16 * b + i) * 64] = o[b][i];
+        dst[64 * 64] = m_run; dst[65 * 64] = l_lane;
       }
-      unsigned pk[2][8];                                         // P^T as packed bf16 pairs
+      __syncthreads();
+      if (kq == 0) {
+        for (int q2 = 1; q2 < KQ; ++q2) {
+          const float* src = xch + (size_t)(rb + q2 * RB) * 66 * 64 + lane;
+          const float m_o = src[64 * 64], l_o = src[65 * 64];
+          const float m_new = fmaxf(m_run, m_o);
+          const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
+          const float a = __builtin_amdgcn_exp2f(m_run - m_sub), bsc = __builtin_amdgcn_exp2f(m_o - m_sub);
+          l_lane = l_lane * a + l_o * bsc;
+          m_run = m_new;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float pr[16];
+          for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          pr[i] = __builtin_amdgcn_exp2f(fmaf(sc[kb][i], cs, -m_sub));
-          l_lane += pr[i];
+            for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a + src[(16 * b + i) * 64] * bsc;
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pk[kb][i] = pack_bf16x2(pr[2 * i], pr[2 * i + 1]);
       }
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          u32x4 pw = {pk[kb][4 * j], pk[kb][4 * j + 1], pk[kb][4 * j + 2], pk[kb][4 * j + 3]};
-          const bf16x8 pf = as_bf16x8(pw);
-          // keys of this k-step for lane-half h: base+4h+{0..3} and base+8+4h+{0..3}
-          const bf16_t* vp = Vb + (32 * kb + 16 * j + 4 * h + (l16 >> 2)) * MF_VSTR + 16 * (c32 >> 4) + 4 * (l16 & 3);
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b));
-            s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b + 8 * MF_VSTR));
-            typedef __attribute__((ext_vector_type(8))) short s16x8;
-            s16x8 vv = {v1[0], v1[1], v1[2], v1[3], v2[0], v2[1], v2[2], v2[3]};
-            o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o[b], 0, 0, 0);
-          }
-        }
     }
 
-    if (t + 1 < NT) store_tile(buf ^ 1, regs);
-    __syncthreads();
-  }
-
-  // ---- split partial: (m, l, O) per (chunk, row, head) ---------------------------------
-  if (wave_active) {
-    const float l_tot = l_lane + __shfl_xor(l_lane, 32);
-    if (row_valid) {
-      const long long slot = ((long long)chunk_id * p.total_rows + (s.row0 + nn)) * p.Hq + hq;
-      float* ap = p.part_acc + slot * MF_D + 4 * h;
+    // ---- epilogue of the piece ------------------------------------------------------------
+    if (kq == 0) {
+      const float l_tot = l_lane + __shfl_xor(l_lane, 32);
+      if (row_valid) {
+        if (whole) {                              // whole item seen here: normalise and store
+          const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+          bf16_t* op = reinterpret_cast<bf16_t*>(p.out) + ((long long)(s.row0 + nn) * p.Hq + hq) * MF_D + 4 * h;
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          f32x4 w = {o[b][4 * a], o[b][4 * a + 1], o[b][4 * a + 2], o[b][4 * a + 3]};
-          *reinterpret_cast<f32x4*>(ap + 32 * b + 8 * a) = w;
+            for (int a = 0; a < 4; ++a) {
+              u32x2 wv = {pack_bf16x2(o[b][4 * a] * inv, o[b][4 * a + 1] * inv),
+                          pack_bf16x2(o[b][4 * a + 2] * inv, o[b][4 * a + 3] * inv)};
+              *reinterpret_cast<u32x2*>(op + 32 * b + 8 * a) = wv;
+            }
+          if (p.lse && h == 0)
+            p.lse[(long long)(s.row0 + nn) * p.Hq + hq] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        } else {                                  // split partial for the combine kernel
+          const long long ps = (long long)slot * ROWS_WG + trow;
+          float* ap = sc_.part_acc + ps * MF_D + 4 * h;
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              f32x4 wv = {o[b][4 * a], o[b][4 * a + 1], o[b][4 * a + 2], o[b][4 * a + 3]};
+              *reinterpret_cast<f32x4*>(ap + 32 * b + 8 * a) = wv;
+            }
+          if (h == 0) { sc_.part_ml[ps * 2] = m_run; sc_.part_ml[ps * 2 + 1] = l_tot; }
         }
-      if (h == 0) { p.part_ml[slot * 2] = m_run; p.part_ml[slot * 2 + 1] = l_tot; }
+      }
     }
+    __syncthreads();                              // LDS is reused by the next piece
+    g += nt;
+    first_piece = false;
   }
 }
 
-size_t attn_mfma_lds_bytes() { return MF_LDS_BYTES; }
+// ---------------------------------------------------------------------------------------
+// Merge the split partials of every item that was cut by a share boundary:
+//   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
+// The pieces of an item sit in slot meta_first, then in the first slot (2w) of every later
+// work-group up to meta_last.  grid (Hkv * rt_max, B).
+// ---------------------------------------------------------------------------------------
+template <int MAXRB>
+__global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
+  constexpr int ROWS_WG = 32 * MAXRB;
+  const int seq = blockIdx.y;
+  const int head = blockIdx.x / sc_.rt_max, rt = blockIdx.x % sc_.rt_max;
+  const SeqInfo s = load_seq(p, seq);
+  const int rows_total = s.n * p.G;
+  if (s.n <= 0 || rt * ROWS_WG >= rows_total) return;
+  const long long meta_idx = ((long long)seq * p.Hkv + head) * sc_.rt_max + rt;
+  const int first_slot = sc_.meta_first[meta_idx];
+  const int wl = sc_.meta_last[meta_idx];
+  const int wf = first_slot >> 1;
+  if ((unsigned)first_slot >= (unsigned)(2 * sc_.num_wgs) || wl < wf || wl >= sc_.num_wgs) return;
+  if (wl == wf) return;                           // one piece: the streaming kernel stored it
+  const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
+  bf16_t* out = reinterpret_cast<bf16_t*>(p.out);
+  for (int e = threadIdx.x; e < rows_here * MF_D; e += 256) {
+    const int trow = e / MF_D, d = e % MF_D;
+    float M = sc_.part_ml[((long long)first_slot * ROWS_WG + trow) * 2];
+    for (int ww = wf + 1; ww <= wl; ++ww) M = fmaxf(M, sc_.part_ml[((long long)(2 * ww) * ROWS_WG + trow) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int ww = wf; ww <= wl; ++ww) {
+      const long long ps = (long long)(ww == wf ? first_slot : 2 * ww) * ROWS_WG + trow;
+      const float mc = sc_.part_ml[ps * 2];
+      if (mc == -INFINITY) continue;
+      const float wgt = exp2f(mc - M);
+      num = fmaf(wgt, sc_.part_acc[ps * MF_D + d], num);
+      den = fmaf(wgt, sc_.part_ml[ps * 2 + 1], den);
+    }
+    const int T_row = rt * ROWS_WG + trow;
+    const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
+    const long long orow = (long long)(s.row0 + nn) * p.Hq + hq;
+    out[orow * MF_D + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+    if (p.lse && d == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
+  }
+}
 
-hipError_t run_attn_mfma(const AttnParams& p, hipStream_t st) {
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+// The MFMA kernel takes bf16, head_dim 128 and power-of-two page sizes >= 16.
+bool attn_mfma_supports(int dtype, int head_dim, int page_size) {
+  return dtype == FD_BF16 && head_dim == MF_D && page_size >= 16 && (page_size & (page_size - 1)) == 0;
+}
+
+int attn_mfma_tile_keys() { return MF_TK; }
+
+// Tile rows one work-group covers for a launch whose largest sequence has `max_tile_rows`.
+int attn_mfma_rows_per_wg(int max_tile_rows) { return max_tile_rows <= 64 ? 64 : 128; }
+
+// Persistent work-groups: two per compute unit.
+int attn_mfma_num_wgs() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0; hipDeviceProp_t pr;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&pr, dev) == hipSuccess && pr.multiProcessorCount > 0)
+      n = 2 * pr.multiProcessorCount;
+    else
+      n = 512;
+  }
+  return n;
+}
+
+// Workspace bytes for (num_wgs, rows per work-group, batch, heads, row blocks).
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, int batch, int hkv, int rt_max, size_t* off_ml, size_t* off_meta) {
+  auto al = [](size_t x) { return (x + 255) / 256 * 256; };
+  size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(float));
+  size_t ml = al((size_t)2 * num_wgs * rows_wg * 2 * sizeof(float));
+  size_t meta = al((size_t)(batch > 0 ? batch : 1) * hkv * rt_max * sizeof(int));
+  if (off_ml) *off_ml = acc;
+  if (off_meta) *off_meta = acc + ml;
+  return acc + ml + 2 * meta;
+}
+
+template <int DBG, int MAXRB>
+static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DBG, MAXRB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)MF_LDS_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  dim3 grid(p.max_chunks, p.Hkv * p.row_tiles, p.B);
-  hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(MF_BLOCK), MF_LDS_BYTES, st, p);
+  hipLaunchKernelGGL((attn_mfma_kernel<DBG, MAXRB>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
+  return hipGetLastError();
+}
+
+// `workspace` must hold attn_mfma_workspace(...) bytes; kv_chunk > 0 asks for shares of that many keys.
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, bool* needs_combine, hipStream_t st) {
+  MfmaSched sc;
+  sc.page_shift = 0;
+  while ((1 << sc.page_shift) < p.page_size) ++sc.page_shift;
+  sc.num_wgs = attn_mfma_num_wgs();
+  sc.min_share = 2;
+  sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
+  const int rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
+  sc.rt_max = (p.max_new_rows * p.G + rows_wg - 1) / rows_wg;
+  if (sc.rt_max < 1) sc.rt_max = 1;
+  size_t off_ml, off_meta;
+  size_t total = attn_mfma_workspace(sc.num_wgs, rows_wg, p.B, p.Hkv, sc.rt_max, &off_ml, &off_meta);
+  char* base = reinterpret_cast<char*>(workspace);
+  sc.part_acc = reinterpret_cast<float*>(base);
+  sc.part_ml = reinterpret_cast<float*>(base + off_ml);
+  sc.meta_first = reinterpret_cast<int*>(base + off_meta);
+  sc.meta_last = reinterpret_cast<int*>(base + off_meta + (total - off_meta) / 2);
+  const bool small = rows_wg == 64;
+  hipError_t e;
+  if (dbg == 1) e = small ? launch_mfma<1, 2>(p, sc, st) : launch_mfma<1, 4>(p, sc, st);
+  else if (dbg == 2) e = small ? launch_mfma<2, 2>(p, sc, st) : launch_mfma<2, 4>(p, sc, st);
+  else e = small ? launch_mfma<0, 2>(p, sc, st) : launch_mfma<0, 4>(p, sc, st);
+  if (e != hipSuccess) return e;
+  *needs_combine = true;
+  return hipSuccess;
+}
+
+hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {
+  MfmaSched sc;
+  sc.page_shift = 0; sc.min_share = 0; sc.fixed_share = 0;
+  sc.num_wgs = attn_mfma_num_wgs();
+  const int rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
+  sc.rt_max = (p.max_new_rows * p.G + rows_wg - 1) / rows_wg;
+  if (sc.rt_max < 1) sc.rt_max = 1;
+  size_t off_ml, off_meta;
+  size_t total = attn_mfma_workspace(sc.num_wgs, rows_wg, p.B, p.Hkv, sc.rt_max, &off_ml, &off_meta);
+  char* base = reinterpret_cast<char*>(workspace);
+  sc.part_acc = reinterpret_cast<float*>(base);
+  sc.part_ml = reinterpret_cast<float*>(base + off_ml);
+  sc.meta_first = reinterpret_cast<int*>(base + off_meta);
+  sc.meta_last = reinterpret_cast<int*>(base + off_meta + (total - off_meta) / 2);
+  dim3 grid(p.Hkv * sc.rt_max, p.B);
+  if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
+  else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
   return hipGetLastError();
 }
 

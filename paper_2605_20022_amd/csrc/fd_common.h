@@ -36,6 +36,13 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Load through the scalar (constant) path: for read-only tables indexed uniformly across the
+// wave (page ids, per-sequence lengths).  The pointer must not alias anything the kernel writes.
+typedef const __attribute__((address_space(4))) int* const_int_ptr;
+__device__ __forceinline__ int sload(const int* p, int idx) {
+  return ((const_int_ptr)(uintptr_t)p)[idx];
+}
+
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
 __device__ __forceinline__ void flag_status(uint32_t* status, uint32_t bit) {
@@ -70,14 +77,22 @@ struct AttnParams {
   float* part_acc;    // [max_chunks][R][Hq][D]
   float* part_ml;     // [max_chunks][R][Hq][2]
   uint32_t* status;
+#ifdef FD_TIMELINE
+  unsigned long long* tl;   // measurement builds: [work-group][8] timestamps
+#endif
 };
 
-__device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) {
+// SCALAR: read through the scalar path (index uniform across the wave) and report bad data
+// through the status word; otherwise plain per-lane loads and no reporting (used when lanes
+// scan different sequences).  Both give identical clamped values.
+template <bool SCALAR>
+__device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i) {
+  auto ld = [&](const int* a, int idx) { return SCALAR ? sload(a, idx) : a[idx]; };
   SeqInfo s;
-  int L = p.kv_len[i];
-  int r0 = p.row_indptr[i], r1 = p.row_indptr[i + 1];
-  int k = p.verify_len[i];
-  int pg0 = p.page_indptr[i], pg1 = p.page_indptr[i + 1];
+  int L = ld(p.kv_len, i);
+  int r0 = ld(p.row_indptr, i), r1 = ld(p.row_indptr, i + 1);
+  int k = ld(p.verify_len, i);
+  int pg0 = ld(p.page_indptr, i), pg1 = ld(p.page_indptr, i + 1);
   uint32_t bad = 0;
   if (L < 0 || L > p.max_kv_len) bad |= FD_DEV_KV_LEN_RANGE;
   s.L = clampi(L, 0, p.max_kv_len);
@@ -89,7 +104,7 @@ __device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) {
   s.k = clampi(k, 0, s.n);
   int v = s.k;
   if (p.mask_vis) {
-    v = p.mask_vis[i];
+    v = ld(p.mask_vis, i);
     if (v < 0 || v > s.k) bad |= FD_DEV_ROWS_RANGE;
     v = clampi(v, 0, s.k);
   }
@@ -101,9 +116,11 @@ __device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) {
     bad |= FD_DEV_PAGE_RANGE;
     s.L = s.npages * p.page_size < s.L ? s.npages * p.page_size : s.L;
   }
-  if (bad) flag_status(p.status, bad);
+  if (SCALAR && bad) flag_status(p.status, bad);
   return s;
 }
+
+__device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) { return load_seq_t<true>(p, i); }
 
 // May new row `r` (0-based within the sequence) look at new row `t`?  Sec. 4.1 mask rules.
 __device__ __forceinline__ bool new_key_visible(int r, int t, int n, int k, int v) {

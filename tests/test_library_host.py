@@ -52,12 +52,14 @@ def _args(**kw):
 def test_attention_workspace_query_and_validation():
     a = _args()
     need = fd.fd_verify_draft_attn_workspace(a)
-    # chunks * rows * heads * (D + 2) floats, chunk count decided by the library
-    per_chunk = 128 * 32 * (128 + 2) * 4
-    assert need >= per_chunk and need % 256 == 0 and (need // per_chunk) <= 64
-    # explicit chunk size fixes the count
-    a.kv_chunk = 4096
-    assert fd.fd_verify_draft_attn_workspace(a) == 8 * per_chunk
+    # MFMA path: two split-partial slots of 128 rows x (D + 2) floats per persistent work-group,
+    # independent of the sequence lengths, plus two small per-item index arrays
+    per_slot = 128 * (128 + 2) * 4
+    assert need % 256 == 0 and need >= 2 * 256 * per_slot and need <= 2 * 2048 * per_slot + (1 << 20)
+    assert fd.fd_verify_draft_attn_workspace(_args(max_kv_len=1 << 20)) == need
+    # scalar path: chunks * rows * heads * (D + 2) floats; an explicit chunk size fixes the count
+    g = _args(flags=fd.FD_ATTN_FORCE_GENERIC, kv_chunk=4096)
+    assert fd.fd_verify_draft_attn_workspace(g) == 8 * 128 * 32 * (128 + 2) * 4
     assert fd.fd_verify_draft_attn_workspace(_args(num_kv_heads=5)) == 0
     assert fd.fd_verify_draft_attn_workspace(_args(head_dim=100)) == 0
     assert fd.fd_verify_draft_attn_workspace(_args(kv_chunk=100)) == 0
