@@ -194,6 +194,8 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--all-configs", action="store_true", help="also report every configuration in per_config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run the library's plain 1 GiB streaming copy (bandwidth yard-stick, counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -207,6 +209,21 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+
+    if args.copy_probe:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
+        for _ in range(3):
+            fd.fd_stream_copy(src, dst)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fd.fd_stream_copy(src, dst)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"probe": "stream_copy", "bytes_read": n, "bytes_written": n, "launches": args.steps + 3,
+                          "ms": round(dt * 1e3, 4), "GBps_read_plus_write": round(2 * n / dt / 1e9, 1)}), flush=True)
+        return
 
     st = Step(fd, args.workload, torch)
     ms_per_step, kern_ms = st.timed(args.steps, args.warmup, profile_kernel=True)

@@ -113,6 +113,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   __shared__ long long sh_ll[MF_BLOCK / 64];
   __shared__ int sh_found[4];
 
+#ifdef FD_TIMELINE
+  const unsigned long long tl0 = wall_clock64();
+  unsigned long long tl1 = 0, tl2 = 0, tl3 = 0; int tl_pieces = 0;
+#define FD_TL(x) x = wall_clock64()
+#else
+#define FD_TL(x)
+#endif
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
   const int w = blockIdx.x;
@@ -193,6 +200,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
   long long g = g0;
   bool first_piece = true;
+  FD_TL(tl1);
   while (g < g1) {
     while (g >= Pt + (long long)T * I) {       // move on to the sequence that holds tile g
       Pt += (long long)T * I;
@@ -335,6 +343,10 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     fetch_pages(tile0 + 1, pg);
     store_tile(0, regs);
     __syncthreads();
+#ifdef FD_TIMELINE
+    if (first_piece) FD_TL(tl2);
+    ++tl_pieces;
+#endif
 
     for (int t = 0; t < nt; ++t) {
       const int tau = tile0 + t;
@@ -502,13 +514,20 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     g += nt;
     first_piece = false;
   }
+#ifdef FD_TIMELINE
+  FD_TL(tl3);
+  if (p.tl && tid == 0) {
+    unsigned long long* o8 = p.tl + (size_t)w * 8;
+    o8[0] = tl0; o8[1] = tl1; o8[2] = tl2; o8[3] = tl3; o8[4] = (unsigned long long)(g1 - g0); o8[5] = tl_pieces;
+  }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------
 // Merge the split partials of every item that was cut by a share boundary:
 //   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
 // The pieces of an item sit in slot meta_first, then in the first slot (2w) of every later
-// work-group up to meta_last.  grid (Hkv * rt_max, B).
+// work-group up to meta_last.  grid (Hkv * rt_max, B, ROWS_WG / 2), 256 threads = 2 rows x 128.
 // ---------------------------------------------------------------------------------------
 template <int MAXRB>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
@@ -526,25 +545,25 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   if (wl == wf) return;                           // one piece: the streaming kernel stored it
   const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
   bf16_t* out = reinterpret_cast<bf16_t*>(p.out);
-  for (int e = threadIdx.x; e < rows_here * MF_D; e += 256) {
-    const int trow = e / MF_D, d = e % MF_D;
-    float M = sc_.part_ml[((long long)first_slot * ROWS_WG + trow) * 2];
-    for (int ww = wf + 1; ww <= wl; ++ww) M = fmaxf(M, sc_.part_ml[((long long)(2 * ww) * ROWS_WG + trow) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int ww = wf; ww <= wl; ++ww) {
-      const long long ps = (long long)(ww == wf ? first_slot : 2 * ww) * ROWS_WG + trow;
-      const float mc = sc_.part_ml[ps * 2];
-      if (mc == -INFINITY) continue;
-      const float wgt = exp2f(mc - M);
-      num = fmaf(wgt, sc_.part_acc[ps * MF_D + d], num);
-      den = fmaf(wgt, sc_.part_ml[ps * 2 + 1], den);
-    }
-    const int T_row = rt * ROWS_WG + trow;
-    const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
-    const long long orow = (long long)(s.row0 + nn) * p.Hq + hq;
-    out[orow * MF_D + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-    if (p.lse && d == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
+  // two tile rows per work-group: thread -> (row, d)
+  const int trow = 2 * blockIdx.z + (threadIdx.x >> 7), d = threadIdx.x & 127;
+  if (trow >= rows_here) return;
+  float M = sc_.part_ml[((long long)first_slot * ROWS_WG + trow) * 2];
+  for (int ww = wf + 1; ww <= wl; ++ww) M = fmaxf(M, sc_.part_ml[((long long)(2 * ww) * ROWS_WG + trow) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int ww = wf; ww <= wl; ++ww) {
+    const long long ps = (long long)(ww == wf ? first_slot : 2 * ww) * ROWS_WG + trow;
+    const float mc = sc_.part_ml[ps * 2];
+    if (mc == -INFINITY) continue;
+    const float wgt = exp2f(mc - M);
+    num = fmaf(wgt, sc_.part_acc[ps * MF_D + d], num);
+    den = fmaf(wgt, sc_.part_ml[ps * 2 + 1], den);
   }
+  const int T_row = rt * ROWS_WG + trow;
+  const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
+  const long long orow = (long long)(s.row0 + nn) * p.Hq + hq;
+  out[orow * MF_D + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+  if (p.lse && d == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -639,7 +658,7 @@ hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream
   sc.part_ml = reinterpret_cast<float*>(base + off_ml);
   sc.meta_first = reinterpret_cast<int*>(base + off_meta);
   sc.meta_last = reinterpret_cast<int*>(base + off_meta + (total - off_meta) / 2);
-  dim3 grid(p.Hkv * sc.rt_max, p.B);
+  dim3 grid(p.Hkv * sc.rt_max, p.B, rows_wg / 2);
   if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
   else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
   return hipGetLastError();
