@@ -13,10 +13,10 @@ hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int 
 bool attn_mfma_supports(int dtype, int head_dim, int page_size);
 int attn_mfma_tile_keys();
 int attn_mfma_rows_per_wg(int max_tile_rows);
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, bool* needs_combine, hipStream_t st);
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, hipStream_t st);
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st);
 int attn_mfma_num_wgs();
-size_t attn_mfma_workspace(int num_wgs, int rows_wg, int batch, int hkv, int rt_max, size_t* off_ml, size_t* off_meta);
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries);
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab, int sampling);
 hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,
                              const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
@@ -101,8 +101,7 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
     // persistent kernel: partial storage depends on the launch size only, not on the lengths
     plan->max_chunks = 1;
     plan->acc_bytes = plan->ml_bytes = 0;
-    plan->total_bytes = fd::attn_mfma_workspace(fd::attn_mfma_num_wgs(), tile_rows, a->batch, a->num_kv_heads,
-                                                plan->row_tiles, nullptr, nullptr);
+    plan->total_bytes = fd::attn_mfma_workspace(fd::attn_mfma_num_wgs(), tile_rows, nullptr, nullptr);
     return FD_OK;
   }
   size_t slots = (size_t)plan->max_chunks * (size_t)(a->total_rows > 0 ? a->total_rows : 1) * a->num_q_heads;
@@ -169,8 +168,7 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   const bool prof = g_prof_events && g_prof_used < g_prof_cap;
   if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
     return fail(FD_ERR_HIP, "hipEventRecord failed");
-  bool mfma_combine = false;
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, (a->flags >> 8) & 3, &mfma_combine, stream)
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, (a->flags >> 8) & 3, stream)
                                : fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
   if (prof) {

@@ -58,11 +58,9 @@ struct MfmaSched {
   int num_wgs;        // persistent work-groups launched
   int min_share;      // automatic shares are never smaller than this many tiles
   int fixed_share;    // > 0: tiles per work-group asked for by the caller
-  int rt_max;         // row blocks per (sequence, head) the meta arrays are laid out for
   float* part_acc;    // [2 * num_wgs][ROWS_WG][D]
   float* part_ml;     // [2 * num_wgs][ROWS_WG][2]
-  int* meta_first;    // [B][Hkv][rt_max]: slot of the item's first piece
-  int* meta_last;     // [B][Hkv][rt_max]: work-group that processed the item's last tile
+  int4* entries;      // [num_wgs]: the split item that ends in this work-group: (seq, head, row block, first slot); seq < 0: none
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
@@ -127,6 +125,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
   const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
   const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
+  if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
 
   // ---- total work, this work-group's share ------------------------------------------------
   long long part = 0;
@@ -217,17 +216,25 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     const int nt = (int)min((long long)(T - tile0), g1 - g);   // tiles of this piece
     const bool whole = (tile0 == 0) && (nt == T);
     const int slot = 2 * w + (first_piece ? 0 : 1);
-    const long long meta_idx = ((long long)seq * p.Hkv + head) * sc_.rt_max + rt;
-    if (tid == 0 && rt < sc_.rt_max) {
-      if (tile0 == 0) sc_.meta_first[meta_idx] = slot;
-      if (tile0 + nt == T) sc_.meta_last[meta_idx] = w;
+    if (tid == 0 && tile0 > 0 && tile0 + nt == T) {
+      // this item started in an earlier work-group and ends here: leave it to the combine kernel.
+      // Its first piece sits in the work-group wf that owns the item's first tile, in slot 2 wf
+      // if the item begins exactly at wf's share, else 2 wf + 1; later pieces are in slots 2 w'.
+      const long long a = Pt + (long long)item * T;
+      int wf = (int)(a * W_eff / total);
+      while ((long long)(wf + 1) * total / W_eff <= a) ++wf;
+      while ((long long)wf * total / W_eff > a) --wf;
+      const int first_slot = 2 * wf + (((long long)wf * total / W_eff == a) ? 0 : 1);
+      sc_.entries[w] = make_int4(seq, head, rt, first_slot);
     }
 
     // ---- wave roles for this item ----------------------------------------------------------
     const int rows_total = s.n * p.G;
     const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
-    const int RB = rows_here <= 32 ? 1 : ((MAXRB == 2 || rows_here <= 64) ? 2 : 4);   // 32-row blocks in use
-    const int KQ = min(4 / RB, MF_BLOCKS);                           // waves sharing a row block
+    // 64-row variant: 1 or 2 row blocks, the waves of a row block split the tile's key blocks;
+    // 128-row variant: wave w owns row block w and every key block (no key split, no merge)
+    const int RB = MAXRB == 4 ? 4 : (rows_here <= 32 ? 1 : 2);      // 32-row blocks in use
+    const int KQ = MAXRB == 4 ? 1 : min(4 / RB, MF_BLOCKS);          // waves sharing a row block
     const int rb = wave % RB, kq = wave / RB;                        // kq >= KQ: no block, idle
     const int trow = rb * 32 + c32;                                  // tile row within the item
     const int T_row = rt * ROWS_WG + trow;
@@ -452,7 +459,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
     float* xch = reinterpret_cast<float*>(lds);                    // [wave][66][64] floats
-    if (KQ > 1) {
+    if (MAXRB != 4 && KQ > 1) {
       if (kq > 0 && kq < KQ) {
         float* dst = xch + (size_t)wave * 66 * 64 + lane;
 #pragma unroll
@@ -526,27 +533,24 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 // ---------------------------------------------------------------------------------------
 // Merge the split partials of every item that was cut by a share boundary:
 //   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
-// The pieces of an item sit in slot meta_first, then in the first slot (2w) of every later
-// work-group up to meta_last.  grid (Hkv * rt_max, B, ROWS_WG / 2), 256 threads = 2 rows x 128.
+// The pieces of an item sit in its first slot, then in the first slot (2w) of every later
+// work-group up to the one it ended in.  grid (num_wgs, ROWS_WG / 2), 256 threads = 2 rows x 128.
 // ---------------------------------------------------------------------------------------
 template <int MAXRB>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
-  const int seq = blockIdx.y;
-  const int head = blockIdx.x / sc_.rt_max, rt = blockIdx.x % sc_.rt_max;
+  const int wl = blockIdx.x;                      // the work-group in which the split item ended
+  const int4 en = sc_.entries[wl];
+  const int seq = en.x, head = en.y, rt = en.z, first_slot = en.w;
+  if (seq < 0 || seq >= p.B) return;
   const SeqInfo s = load_seq(p, seq);
   const int rows_total = s.n * p.G;
-  if (s.n <= 0 || rt * ROWS_WG >= rows_total) return;
-  const long long meta_idx = ((long long)seq * p.Hkv + head) * sc_.rt_max + rt;
-  const int first_slot = sc_.meta_first[meta_idx];
-  const int wl = sc_.meta_last[meta_idx];
   const int wf = first_slot >> 1;
-  if ((unsigned)first_slot >= (unsigned)(2 * sc_.num_wgs) || wl < wf || wl >= sc_.num_wgs) return;
-  if (wl == wf) return;                           // one piece: the streaming kernel stored it
+  if (s.n <= 0 || rt < 0 || rt * ROWS_WG >= rows_total || head < 0 || head >= p.Hkv || first_slot < 0 || wf >= wl) return;
   const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
   bf16_t* out = reinterpret_cast<bf16_t*>(p.out);
   // two tile rows per work-group: thread -> (row, d)
-  const int trow = 2 * blockIdx.z + (threadIdx.x >> 7), d = threadIdx.x & 127;
+  const int trow = 2 * blockIdx.y + (threadIdx.x >> 7), d = threadIdx.x & 127;
   if (trow >= rows_here) return;
   float M = sc_.part_ml[((long long)first_slot * ROWS_WG + trow) * 2];
   for (int ww = wf + 1; ww <= wl; ++ww) M = fmaxf(M, sc_.part_ml[((long long)(2 * ww) * ROWS_WG + trow) * 2]);
@@ -592,15 +596,30 @@ int attn_mfma_num_wgs() {
   return n;
 }
 
-// Workspace bytes for (num_wgs, rows per work-group, batch, heads, row blocks).
-size_t attn_mfma_workspace(int num_wgs, int rows_wg, int batch, int hkv, int rt_max, size_t* off_ml, size_t* off_meta) {
+// Workspace bytes for (num_wgs, rows per work-group); offsets of the (m, l) array and the entries.
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries) {
   auto al = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(float));
   size_t ml = al((size_t)2 * num_wgs * rows_wg * 2 * sizeof(float));
-  size_t meta = al((size_t)(batch > 0 ? batch : 1) * hkv * rt_max * sizeof(int));
+  size_t en = al((size_t)num_wgs * sizeof(int4));
   if (off_ml) *off_ml = acc;
-  if (off_meta) *off_meta = acc + ml;
-  return acc + ml + 2 * meta;
+  if (off_entries) *off_entries = acc + ml;
+  return acc + ml + en;
+}
+
+static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaSched& sc, int& rows_wg) {
+  sc.page_shift = 0;
+  while ((1 << sc.page_shift) < p.page_size) ++sc.page_shift;
+  sc.num_wgs = attn_mfma_num_wgs();
+  sc.min_share = 2;
+  sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
+  rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
+  size_t off_ml, off_en;
+  attn_mfma_workspace(sc.num_wgs, rows_wg, &off_ml, &off_en);
+  char* base = reinterpret_cast<char*>(workspace);
+  sc.part_acc = reinterpret_cast<float*>(base);
+  sc.part_ml = reinterpret_cast<float*>(base + off_ml);
+  sc.entries = reinterpret_cast<int4*>(base + off_en);
 }
 
 template <int DBG, int MAXRB>
@@ -617,48 +636,19 @@ static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStrea
 }
 
 // `workspace` must hold attn_mfma_workspace(...) bytes; kv_chunk > 0 asks for shares of that many keys.
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, bool* needs_combine, hipStream_t st) {
-  MfmaSched sc;
-  sc.page_shift = 0;
-  while ((1 << sc.page_shift) < p.page_size) ++sc.page_shift;
-  sc.num_wgs = attn_mfma_num_wgs();
-  sc.min_share = 2;
-  sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
-  const int rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
-  sc.rt_max = (p.max_new_rows * p.G + rows_wg - 1) / rows_wg;
-  if (sc.rt_max < 1) sc.rt_max = 1;
-  size_t off_ml, off_meta;
-  size_t total = attn_mfma_workspace(sc.num_wgs, rows_wg, p.B, p.Hkv, sc.rt_max, &off_ml, &off_meta);
-  char* base = reinterpret_cast<char*>(workspace);
-  sc.part_acc = reinterpret_cast<float*>(base);
-  sc.part_ml = reinterpret_cast<float*>(base + off_ml);
-  sc.meta_first = reinterpret_cast<int*>(base + off_meta);
-  sc.meta_last = reinterpret_cast<int*>(base + off_meta + (total - off_meta) / 2);
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, hipStream_t st) {
+  MfmaSched sc; int rows_wg;
+  fill_sched(p, workspace, kv_chunk, sc, rows_wg);
   const bool small = rows_wg == 64;
-  hipError_t e;
-  if (dbg == 1) e = small ? launch_mfma<1, 2>(p, sc, st) : launch_mfma<1, 4>(p, sc, st);
-  else if (dbg == 2) e = small ? launch_mfma<2, 2>(p, sc, st) : launch_mfma<2, 4>(p, sc, st);
-  else e = small ? launch_mfma<0, 2>(p, sc, st) : launch_mfma<0, 4>(p, sc, st);
-  if (e != hipSuccess) return e;
-  *needs_combine = true;
-  return hipSuccess;
+  if (dbg == 1) return small ? launch_mfma<1, 2>(p, sc, st) : launch_mfma<1, 4>(p, sc, st);
+  if (dbg == 2) return small ? launch_mfma<2, 2>(p, sc, st) : launch_mfma<2, 4>(p, sc, st);
+  return small ? launch_mfma<0, 2>(p, sc, st) : launch_mfma<0, 4>(p, sc, st);
 }
 
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {
-  MfmaSched sc;
-  sc.page_shift = 0; sc.min_share = 0; sc.fixed_share = 0;
-  sc.num_wgs = attn_mfma_num_wgs();
-  const int rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
-  sc.rt_max = (p.max_new_rows * p.G + rows_wg - 1) / rows_wg;
-  if (sc.rt_max < 1) sc.rt_max = 1;
-  size_t off_ml, off_meta;
-  size_t total = attn_mfma_workspace(sc.num_wgs, rows_wg, p.B, p.Hkv, sc.rt_max, &off_ml, &off_meta);
-  char* base = reinterpret_cast<char*>(workspace);
-  sc.part_acc = reinterpret_cast<float*>(base);
-  sc.part_ml = reinterpret_cast<float*>(base + off_ml);
-  sc.meta_first = reinterpret_cast<int*>(base + off_meta);
-  sc.meta_last = reinterpret_cast<int*>(base + off_meta + (total - off_meta) / 2);
-  dim3 grid(p.Hkv * sc.rt_max, p.B, rows_wg / 2);
+  MfmaSched sc; int rows_wg;
+  fill_sched(p, workspace, 0, sc, rows_wg);
+  dim3 grid(sc.num_wgs, rows_wg / 2);
   if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
   else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
   return hipGetLastError();
