@@ -256,7 +256,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     // ---- tiles of the piece: [tile0, tile0 + nt) of the item; the first n_ct_all are cached ----
     const int n_ct_all = (s.L + MF_TK - 1) / MF_TK;
     const int c1 = s.L;
-    const long long ld_off = (long long)head * p.sh + (long long)ld_key * p.st + ld_col;
+    const long long head_off = (long long)head * p.sh;                                  // uniform
+    const unsigned lane_boff = (unsigned)(2 * ((long long)ld_key * p.st + ld_col));       // this lane's bytes within a 16-key slab
     const int* pi = p.page_indices + s.page0;
 
     // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
@@ -278,46 +279,41 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       }
     };
 
+    // One 16-key group = 16 rows of 256 B at a fixed pitch from a base that is the same for the
+    // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
+    // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows at or past
+    // `valid` lie outside the descriptor, so the hardware returns zeros for them.
+    auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int valid, long long pitch, unsigned lane_off,
+                         u32x4& rk, u32x4& rv) {
+      const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
+      const int nrec = v16 > 0 ? (int)(((long long)(v16 - 1) * pitch + MF_D) * 2) : 0;
+      __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
+      __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
+      rk = __builtin_amdgcn_raw_buffer_load_b128(rk_, lane_off, 0, 2);      // aux 2: streaming (nt)
+      rv = __builtin_amdgcn_raw_buffer_load_b128(rv_, lane_off, 0, 2);
+    };
+    const long long new_pitch = (long long)p.Hkv * MF_D;
+    const unsigned lane_off_new = (unsigned)(2 * ((long long)ld_key * new_pitch + ld_col));
     auto load_tile = [&](int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
-      const u32x4 z = {0u, 0u, 0u, 0u};
       if (tau < n_ct_all) {
         const int base = tau * MF_TK;
         bool bad = false;
-        if (base + MF_TK <= c1) {                // full tile: no per-key guards
 #pragma unroll
-          for (int j = 0; j < MF_GROUPS; ++j) {
-            int ph = pg[j];
-            if ((unsigned)ph >= (unsigned)p.num_pages) { bad = true; ph = 0; }
-            long long off = (long long)ph * p.sp + (long long)((base + 16 * j) & page_mask) * p.st + ld_off;
-            r.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + off));
-            r.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vc + off));
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < MF_GROUPS; ++j) {
-            int gs = base + 16 * j;
-            int ph = pg[j];
-            if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < c1); ph = 0; }
-            r.k[j] = z; r.v[j] = z;
-            if (gs + ld_key < c1) {
-              long long off = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + ld_off;
-              r.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + off));
-              r.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vc + off));
-            }
-          }
+        for (int j = 0; j < MF_GROUPS; ++j) {
+          const int gs = base + 16 * j;
+          int ph = pg[j];
+          if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < c1); ph = 0; }
+          const long long ub = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + head_off;
+          load_rows(Kc + ub, Vc + ub, c1 - gs, p.st, lane_boff, r.k[j], r.v[j]);
         }
         if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
       } else {
         const int base = (tau - n_ct_all) * MF_TK;
 #pragma unroll
         for (int j = 0; j < MF_GROUPS; ++j) {
-          int key = base + 16 * j + ld_key;
-          r.k[j] = z; r.v[j] = z;
-          if (key < s.n) {
-            long long off = ((long long)(s.row0 + key) * p.Hkv + head) * MF_D + ld_col;
-            r.k[j] = *reinterpret_cast<const u32x4*>(Kn + off);
-            r.v[j] = *reinterpret_cast<const u32x4*>(Vn + off);
-          }
+          const int key0 = base + 16 * j;
+          const long long ub = ((long long)(s.row0 + key0) * p.Hkv + head) * MF_D;
+          load_rows(Kn + ub, Vn + ub, s.n - key0, new_pitch, lane_off_new, r.k[j], r.v[j]);
         }
       }
     };
@@ -344,24 +340,28 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     int pg[MF_GROUPS];
 #pragma unroll
     for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
-    TileRegs regs;
+    // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
+    // (already requested one iteration ago) is written to the other LDS buffer and tile t+2 is
+    // requested.  rA / rB alternate between "being stored" and "being loaded".
+    TileRegs rA, rB;
     fetch_pages(tile0, pg);
-    load_tile(tile0, pg, regs);
+    load_tile(tile0, pg, rA);
     fetch_pages(tile0 + 1, pg);
-    store_tile(0, regs);
+    store_tile(0, rA);
+    if (nt > 1 && DBG != 2) { load_tile(tile0 + 1, pg, rA); fetch_pages(tile0 + 2, pg); }
     __syncthreads();
 #ifdef FD_TIMELINE
     if (first_piece) FD_TL(tl2);
     ++tl_pieces;
 #endif
 
-    for (int t = 0; t < nt; ++t) {
+    auto iteration = [&](int t, TileRegs& r_store, TileRegs& r_load) {
       const int tau = tile0 + t;
       const bf16_t* Ks = lds + (t & 1) * MF_BUF_ELEMS;
       const bf16_t* Vs = Ks + MF_K_ELEMS;
-      if (t + 1 < nt && DBG != 2) {
-        load_tile(tau + 1, pg, regs);
-        fetch_pages(tau + 2, pg);
+      if (t + 2 < nt && DBG != 2) {
+        load_tile(tau + 2, pg, r_load);
+        fetch_pages(tau + 3, pg);
       }
 
       // valid keys in this tile and whether the visibility rule has to be evaluated
@@ -453,8 +453,12 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
         }
       }
 
-      if (t + 1 < nt && DBG != 2) store_tile((t + 1) & 1, regs);
+      if (t + 1 < nt && DBG != 2) store_tile((t + 1) & 1, r_store);
       __syncthreads();                           // tile t fully consumed, tile t+1 visible
+    };
+    for (int t = 0; t < nt; t += 2) {
+      iteration(t, rA, rB);
+      if (t + 1 < nt) iteration(t + 1, rB, rA);
     }
 
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
