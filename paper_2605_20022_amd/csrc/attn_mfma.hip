@@ -194,140 +194,186 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     s.npages = __builtin_amdgcn_readfirstlane(s.npages);
     return s;
   };
-  SeqInfo s = get_seq(seq);
-  int T, I; seq_shape(p, s, ROWS_WG, T, I);
+  // ---- walk over the share, one piece (run of tiles inside one item) at a time ----------------
+  // The walk state (sequence, its shape, tiles before it) only moves forward.
+  SeqInfo ws = get_seq(seq);
+  int T, I; seq_shape(p, ws, ROWS_WG, T, I);
 
-  long long g = g0;
-  bool first_piece = true;
-  FD_TL(tl1);
-  while (g < g1) {
-    while (g >= Pt + (long long)T * I) {       // move on to the sequence that holds tile g
+  struct Piece {
+    SeqInfo s;                  // the sequence (scalar registers)
+    int seq, head, rt;          // item
+    int tile0, nt, T;           // tiles [tile0, tile0 + nt) of the item's T
+    int n_ct_all;               // cached tiles of the item (the rest are tiles of new rows)
+    long long head_off;         // head * cache_stride_head
+    const int* pi;              // the sequence's page list
+    long long item_a;           // global index of the item's first tile
+  };
+  // descriptor of the piece that starts at global tile g (g < g1); false if the data ran out
+  auto make_piece = [&](long long g, Piece& pc) -> bool {
+    while (g >= Pt + (long long)T * I) {
       Pt += (long long)T * I;
       ++seq;
-      if (seq >= p.B) return;
-      s = get_seq(seq);
-      seq_shape(p, s, ROWS_WG, T, I);
+      if (seq >= p.B) return false;
+      ws = get_seq(seq);
+      seq_shape(p, ws, ROWS_WG, T, I);
     }
     const long long local = g - Pt;
     const int item = (int)(local / T);
-    const int tile0 = (int)(local - (long long)item * T);
     const int RT = I / p.Hkv;
-    const int head = item / RT, rt = item - head * RT;
-    const int nt = (int)min((long long)(T - tile0), g1 - g);   // tiles of this piece
-    const bool whole = (tile0 == 0) && (nt == T);
+    pc.s = ws; pc.seq = seq; pc.T = T;
+    pc.head = item / RT; pc.rt = item - pc.head * RT;
+    pc.tile0 = (int)(local - (long long)item * T);
+    pc.nt = (int)min((long long)(T - pc.tile0), g1 - g);
+    pc.n_ct_all = (ws.L + MF_TK - 1) / MF_TK;
+    pc.head_off = (long long)pc.head * p.sh;
+    pc.pi = p.page_indices + ws.page0;
+    pc.item_a = Pt + (long long)item * T;
+    return true;
+  };
+
+  const unsigned lane_boff = (unsigned)(2 * ((long long)ld_key * p.st + ld_col));       // bytes within a cached 16-key slab
+  const long long new_pitch = (long long)p.Hkv * MF_D;
+  const unsigned lane_off_new = (unsigned)(2 * ((long long)ld_key * new_pitch + ld_col)); // bytes within 16 new rows
+
+  // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
+  // fetched with scalar loads ahead of time and range-checked when the addresses are formed.
+  auto fetch_pages = [&](const Piece& pc, int tau, int (&pg)[MF_GROUPS]) {
+    if (tau < pc.n_ct_all) {
+      const int base = tau * MF_TK;
+      if (base + MF_TK <= pc.s.L) {
+#pragma unroll
+        for (int j = 0; j < MF_GROUPS; ++j)
+          pg[j] = sload(pc.pi, __builtin_amdgcn_readfirstlane((base + 16 * j) >> sc_.page_shift));
+      } else {
+#pragma unroll
+        for (int j = 0; j < MF_GROUPS; ++j) {
+          int gs = base + 16 * j;
+          pg[j] = gs < pc.s.L ? sload(pc.pi, __builtin_amdgcn_readfirstlane(gs >> sc_.page_shift)) : 0;
+        }
+      }
+    }
+  };
+  // One 16-key group = 16 rows of 256 B at a fixed pitch from a base that is the same for the
+  // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
+  // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows at or past
+  // `valid` lie outside the descriptor, so the hardware returns zeros for them.
+  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int valid, long long pitch, unsigned lane_off,
+                       u32x4& rk, u32x4& rv) {
+    const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
+    const int nrec = v16 > 0 ? (int)(((long long)(v16 - 1) * pitch + MF_D) * 2) : 0;
+    __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
+    __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
+    rk = __builtin_amdgcn_raw_buffer_load_b128(rk_, lane_off, 0, 2);      // aux 2: streaming (nt)
+    rv = __builtin_amdgcn_raw_buffer_load_b128(rv_, lane_off, 0, 2);
+  };
+  auto load_tile = [&](const Piece& pc, int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
+    if (tau < pc.n_ct_all) {
+      const int base = tau * MF_TK;
+      bool bad = false;
+#pragma unroll
+      for (int j = 0; j < MF_GROUPS; ++j) {
+        const int gs = base + 16 * j;
+        int ph = pg[j];
+        if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < pc.s.L); ph = 0; }
+        const long long ub = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + pc.head_off;
+        load_rows(Kc + ub, Vc + ub, pc.s.L - gs, p.st, lane_boff, r.k[j], r.v[j]);
+      }
+      if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
+    } else {
+      const int base = (tau - pc.n_ct_all) * MF_TK;
+#pragma unroll
+      for (int j = 0; j < MF_GROUPS; ++j) {
+        const int key0 = base + 16 * j;
+        const long long ub = ((long long)(pc.s.row0 + key0) * p.Hkv + pc.head) * MF_D;
+        load_rows(Kn + ub, Vn + ub, pc.s.n - key0, new_pitch, lane_off_new, r.k[j], r.v[j]);
+      }
+    }
+  };
+  auto store_tile = [&](int buf, const TileRegs& r) {
+    bf16_t* Kb = lds + buf * MF_BUF_ELEMS;
+    bf16_t* Vb = Kb + MF_K_ELEMS;
+#pragma unroll
+    for (int j = 0; j < MF_GROUPS; ++j) {
+      int row = 16 * j + ld_key;
+      *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[j];
+      *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[j];
+    }
+  };
+
+  // Per-lane view of a piece: which query row this lane owns and the wave's role.
+  struct Lane {
+    int RB, KQ, rb, kq, trow, nn, hq;
+    bool row_valid, wave_has_rows;
+  };
+  auto make_lane = [&](const Piece& pc) {
+    Lane ln;
+    const int rows_total = pc.s.n * p.G;
+    const int rows_here = min(ROWS_WG, rows_total - pc.rt * ROWS_WG);
+    // 64-row variant: 1 or 2 row blocks, the waves of a row block split the tile's key blocks;
+    // 128-row variant: wave w owns row block w and every key block (no key split, no merge)
+    ln.RB = MAXRB == 4 ? 4 : (rows_here <= 32 ? 1 : 2);
+    ln.KQ = MAXRB == 4 ? 1 : min(4 / ln.RB, MF_BLOCKS);
+    ln.rb = wave % ln.RB; ln.kq = wave / ln.RB;                   // kq >= KQ: no block, idle
+    ln.trow = ln.rb * 32 + c32;
+    const int T_row = pc.rt * ROWS_WG + ln.trow;
+    ln.row_valid = T_row < rows_total;
+    ln.wave_has_rows = pc.rt * ROWS_WG + ln.rb * 32 < rows_total;
+    ln.nn = T_row / p.G;
+    ln.hq = pc.head * p.G + T_row % p.G;
+    return ln;
+  };
+
+  bf16x8 qf[8];
+  int pg[MF_GROUPS];
+#pragma unroll
+  for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
+  TileRegs rA, rB;
+  // Everything a piece needs from memory before its first tile can be multiplied: page ids, the
+  // first two tiles (into rA, rB) and this lane's query row.  Issued as early as possible - for
+  // every piece but the first, while the previous piece is still being merged and stored.
+  auto start_piece = [&](const Piece& pc, const Lane& ln) {
+    fetch_pages(pc, pc.tile0, pg);
+    const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(pc.s.row0 + (ln.row_valid ? ln.nn : 0)) * p.Hq + ln.hq) * MF_D + 8 * h;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      u32x4 wq = {0u, 0u, 0u, 0u};
+      if (ln.row_valid) wq = *reinterpret_cast<const u32x4*>(qp + 16 * st);
+      qf[st] = as_bf16x8(wq);
+    }
+    load_tile(pc, pc.tile0, pg, rA);
+    if (pc.nt > 1 && DBG != 2) {
+      fetch_pages(pc, pc.tile0 + 1, pg);
+      load_tile(pc, pc.tile0 + 1, pg, rB);
+    }
+    fetch_pages(pc, pc.tile0 + 2, pg);
+  };
+
+  long long g = g0;
+  bool first_piece = true;
+  Piece cur;
+  if (!make_piece(g, cur)) return;
+  Lane ln = make_lane(cur);
+  start_piece(cur, ln);
+  FD_TL(tl1);
+  bool have = true;
+  while (have) {
+    const SeqInfo& s = cur.s;
+    const int tile0 = cur.tile0, nt = cur.nt, n_ct_all = cur.n_ct_all, c1 = cur.s.L;
+    const bool whole = (tile0 == 0) && (nt == cur.T);
     const int slot = 2 * w + (first_piece ? 0 : 1);
-    if (tid == 0 && tile0 > 0 && tile0 + nt == T) {
+    if (tid == 0 && tile0 > 0 && tile0 + nt == cur.T) {
       // this item started in an earlier work-group and ends here: leave it to the combine kernel.
       // Its first piece sits in the work-group wf that owns the item's first tile, in slot 2 wf
       // if the item begins exactly at wf's share, else 2 wf + 1; later pieces are in slots 2 w'.
-      const long long a = Pt + (long long)item * T;
+      const long long a = cur.item_a;
       int wf = (int)(a * W_eff / total);
       while ((long long)(wf + 1) * total / W_eff <= a) ++wf;
       while ((long long)wf * total / W_eff > a) --wf;
       const int first_slot = 2 * wf + (((long long)wf * total / W_eff == a) ? 0 : 1);
-      sc_.entries[w] = make_int4(seq, head, rt, first_slot);
+      sc_.entries[w] = make_int4(cur.seq, cur.head, cur.rt, first_slot);
     }
-
-    // ---- wave roles for this item ----------------------------------------------------------
-    const int rows_total = s.n * p.G;
-    const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
-    // 64-row variant: 1 or 2 row blocks, the waves of a row block split the tile's key blocks;
-    // 128-row variant: wave w owns row block w and every key block (no key split, no merge)
-    const int RB = MAXRB == 4 ? 4 : (rows_here <= 32 ? 1 : 2);      // 32-row blocks in use
-    const int KQ = MAXRB == 4 ? 1 : min(4 / RB, MF_BLOCKS);          // waves sharing a row block
-    const int rb = wave % RB, kq = wave / RB;                        // kq >= KQ: no block, idle
-    const int trow = rb * 32 + c32;                                  // tile row within the item
-    const int T_row = rt * ROWS_WG + trow;
-    const bool row_valid = T_row < rows_total;
-    const bool wave_has_rows = rt * ROWS_WG + rb * 32 < rows_total;
-    const int nn = T_row / p.G;                                      // new-row index within the sequence
-    const int hq = head * p.G + T_row % p.G;
-    bf16x8 qf[8];
-    {
-      const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(s.row0 + (row_valid ? nn : 0)) * p.Hq + hq) * MF_D + 8 * h;
-#pragma unroll
-      for (int st = 0; st < 8; ++st) {
-        u32x4 wq = {0u, 0u, 0u, 0u};
-        if (row_valid) wq = *reinterpret_cast<const u32x4*>(qp + 16 * st);
-        qf[st] = as_bf16x8(wq);
-      }
-    }
-
-    // ---- tiles of the piece: [tile0, tile0 + nt) of the item; the first n_ct_all are cached ----
-    const int n_ct_all = (s.L + MF_TK - 1) / MF_TK;
-    const int c1 = s.L;
-    const long long head_off = (long long)head * p.sh;                                  // uniform
-    const unsigned lane_boff = (unsigned)(2 * ((long long)ld_key * p.st + ld_col));       // this lane's bytes within a 16-key slab
-    const int* pi = p.page_indices + s.page0;
-
-    // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
-    // fetched with scalar loads one tile ahead and range-checked when the addresses are formed.
-    auto fetch_pages = [&](int tau, int (&pg)[MF_GROUPS]) {
-      if (tau < n_ct_all) {
-        const int base = tau * MF_TK;
-        if (base + MF_TK <= c1) {
-#pragma unroll
-          for (int j = 0; j < MF_GROUPS; ++j)
-            pg[j] = sload(pi, __builtin_amdgcn_readfirstlane((base + 16 * j) >> sc_.page_shift));
-        } else {
-#pragma unroll
-          for (int j = 0; j < MF_GROUPS; ++j) {
-            int gs = base + 16 * j;
-            pg[j] = gs < c1 ? sload(pi, __builtin_amdgcn_readfirstlane(gs >> sc_.page_shift)) : 0;
-          }
-        }
-      }
-    };
-
-    // One 16-key group = 16 rows of 256 B at a fixed pitch from a base that is the same for the
-    // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
-    // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows at or past
-    // `valid` lie outside the descriptor, so the hardware returns zeros for them.
-    auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int valid, long long pitch, unsigned lane_off,
-                         u32x4& rk, u32x4& rv) {
-      const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
-      const int nrec = v16 > 0 ? (int)(((long long)(v16 - 1) * pitch + MF_D) * 2) : 0;
-      __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
-      __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
-      rk = __builtin_amdgcn_raw_buffer_load_b128(rk_, lane_off, 0, 2);      // aux 2: streaming (nt)
-      rv = __builtin_amdgcn_raw_buffer_load_b128(rv_, lane_off, 0, 2);
-    };
-    const long long new_pitch = (long long)p.Hkv * MF_D;
-    const unsigned lane_off_new = (unsigned)(2 * ((long long)ld_key * new_pitch + ld_col));
-    auto load_tile = [&](int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
-      if (tau < n_ct_all) {
-        const int base = tau * MF_TK;
-        bool bad = false;
-#pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j) {
-          const int gs = base + 16 * j;
-          int ph = pg[j];
-          if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < c1); ph = 0; }
-          const long long ub = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + head_off;
-          load_rows(Kc + ub, Vc + ub, c1 - gs, p.st, lane_boff, r.k[j], r.v[j]);
-        }
-        if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
-      } else {
-        const int base = (tau - n_ct_all) * MF_TK;
-#pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j) {
-          const int key0 = base + 16 * j;
-          const long long ub = ((long long)(s.row0 + key0) * p.Hkv + head) * MF_D;
-          load_rows(Kn + ub, Vn + ub, s.n - key0, new_pitch, lane_off_new, r.k[j], r.v[j]);
-        }
-      }
-    };
-
-    auto store_tile = [&](int buf, const TileRegs& r) {
-      bf16_t* Kb = lds + buf * MF_BUF_ELEMS;
-      bf16_t* Vb = Kb + MF_K_ELEMS;
-#pragma unroll
-      for (int j = 0; j < MF_GROUPS; ++j) {
-        int row = 16 * j + ld_key;
-        *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[j];
-        *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[j];
-      }
-    };
+    const int RB = ln.RB, KQ = ln.KQ, rb = ln.rb, kq = ln.kq, trow = ln.trow, nn = ln.nn, hq = ln.hq;
+    const bool row_valid = ln.row_valid, wave_has_rows = ln.wave_has_rows;
 
     // ---- running softmax state: one query row per lane ------------------------------------
     float m_run = -INFINITY, l_lane = 0.f;
@@ -337,31 +383,22 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
-    int pg[MF_GROUPS];
-#pragma unroll
-    for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
-    // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
-    // (already requested one iteration ago) is written to the other LDS buffer and tile t+2 is
-    // requested.  rA / rB alternate between "being stored" and "being loaded".
-    TileRegs rA, rB;
-    fetch_pages(tile0, pg);
-    load_tile(tile0, pg, rA);
-    fetch_pages(tile0 + 1, pg);
-    store_tile(0, rA);
-    if (nt > 1 && DBG != 2) { load_tile(tile0 + 1, pg, rA); fetch_pages(tile0 + 2, pg); }
+    store_tile(0, rA);                             // waits for the piece's first tile
     __syncthreads();
 #ifdef FD_TIMELINE
     if (first_piece) FD_TL(tl2);
     ++tl_pieces;
 #endif
 
+    // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
+    // (requested earlier) is written to the other LDS buffer and tile t+2 is requested.
     auto iteration = [&](int t, TileRegs& r_store, TileRegs& r_load) {
       const int tau = tile0 + t;
       const bf16_t* Ks = lds + (t & 1) * MF_BUF_ELEMS;
       const bf16_t* Vs = Ks + MF_K_ELEMS;
       if (t + 2 < nt && DBG != 2) {
-        load_tile(tau + 2, pg, r_load);
-        fetch_pages(tau + 3, pg);
+        load_tile(cur, tau + 2, pg, r_load);
+        fetch_pages(cur, tau + 3, pg);
       }
 
       // valid keys in this tile and whether the visibility rule has to be evaluated
@@ -457,9 +494,15 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       __syncthreads();                           // tile t fully consumed, tile t+1 visible
     };
     for (int t = 0; t < nt; t += 2) {
-      iteration(t, rA, rB);
-      if (t + 1 < nt) iteration(t + 1, rB, rA);
+      iteration(t, rB, rA);
+      if (t + 1 < nt) iteration(t + 1, rA, rB);
     }
+
+    // ---- next piece: get its loads going before this one is merged and stored --------------
+    g += nt;
+    Piece nxt; Lane ln_next = ln;
+    have = (g < g1) && make_piece(g, nxt);
+    if (have) { ln_next = make_lane(nxt); start_piece(nxt, ln_next); }
 
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
     float* xch = reinterpret_cast<float*>(lds);                    // [wave][66][64] floats
@@ -522,8 +565,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       }
     }
     __syncthreads();                              // LDS is reused by the next piece
-    g += nt;
     first_piece = false;
+    if (have) { cur = nxt; ln = ln_next; }
   }
 #ifdef FD_TIMELINE
   FD_TL(tl3);
