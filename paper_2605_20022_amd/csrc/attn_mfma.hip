@@ -95,9 +95,9 @@ __device__ __forceinline__ long long uniform_ll(long long v) {
   return (long long)(((unsigned long long)hi << 32) | lo);
 }
 
-__device__ __forceinline__ long long wave_incl_scan(long long v, int lane) {
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) { long long o = __shfl_up(v, off); if (lane >= off) v += o; }
+  for (int off = 1; off < 64; off <<= 1) { int o = __shfl_up(v, off); if (lane >= off) v += o; }
   return v;
 }
 
@@ -108,15 +108,18 @@ template <int DBG, int MAXRB>
 __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
-  __shared__ long long sh_ll[MF_BLOCK / 64];
-  __shared__ int sh_found[4];
+  __shared__ int sh_w[MF_BLOCK / 64];
+  __shared__ int sh_found[12];
 
 #ifdef FD_TIMELINE
   const unsigned long long tl0 = wall_clock64();
   unsigned long long tl1 = 0, tl2 = 0, tl3 = 0; int tl_pieces = 0;
 #define FD_TL(x) x = wall_clock64()
+  // stamp k (0..3) of piece tl_pieces-1 (first four pieces): written straight to memory by thread 0
+#define FD_TLP(k) do { if (p.tl && tid == 0 && tl_pieces >= 1 && tl_pieces <= 4) p.tl[8 * 1024 + (size_t)w * 16 + 4 * (tl_pieces - 1) + (k)] = wall_clock64(); } while (0)
 #else
 #define FD_TL(x)
+#define FD_TLP(k)
 #endif
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
@@ -127,59 +130,107 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
   if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
 
-  // ---- total work, this work-group's share ------------------------------------------------
-  long long part = 0;
-  for (int i = tid; i < p.B; i += MF_BLOCK) {
-    SeqInfo s = load_seq_t<false>(p, i);
-    int T, I; seq_shape(p, s, ROWS_WG, T, I);
-    part += (long long)T * I;
-  }
-  part = wave_incl_scan(part, lane);
-  if (lane == 63) sh_ll[wave] = part;
-  __syncthreads();
-  long long total = 0;
-  for (int q = 0; q < MF_BLOCK / 64; ++q) total += sh_ll[q];
-  total = uniform_ll(total);
-  __syncthreads();
-  if (total <= 0) return;
-  long long want = sc_.fixed_share > 0 ? sc_.fixed_share : max((long long)sc_.min_share, (total + sc_.num_wgs - 1) / sc_.num_wgs);
-  long long weff_ll = (total + want - 1) / want;
-  const int W_eff = (int)min((long long)sc_.num_wgs, weff_ll);
-  if (w >= W_eff) return;
-  const long long g0 = (long long)w * total / W_eff;
-  const long long g1 = (long long)(w + 1) * total / W_eff;
-  if (g1 <= g0) return;
-
-  // ---- sequence that contains tile g0: block-wide prefix scan over the batch ---------------
-  {
-    long long base_t = 0;
+  // ---- total work, this work-group's share, and the sequence in which the share starts -------
+  // Tile counts fit 32 bits (the host checks the bound), so no 64-bit division is needed.
+  // share w = [w q + floor(w r / W), ...) with q, r = total / W, total % W: equal to floor(w total / W)
+  unsigned total = 0, sh_q = 0, sh_r = 0;
+  int W_eff = 0;
+  auto plan_shares = [&]() {
+    const unsigned want = sc_.fixed_share > 0 ? (unsigned)sc_.fixed_share
+                                              : max((unsigned)sc_.min_share, (total + sc_.num_wgs - 1) / (unsigned)sc_.num_wgs);
+    const unsigned weff = (total + want - 1) / want;
+    W_eff = (int)min((unsigned)sc_.num_wgs, weff);
+    sh_q = total / (unsigned)W_eff; sh_r = total % (unsigned)W_eff;
+  };
+  auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
+  unsigned g0 = 0, g1 = 0, Pt = 0;
+  int seq = -1;
+  SeqInfo ws;
+  if (p.B <= MF_BLOCK) {
+    // one pass: thread i keeps sequence i in registers, the owner of tile g0 hands it over through LDS
+    SeqInfo s_mine = {}; uint32_t bad = 0; int vt = 0;
+    if (tid < p.B) {
+      s_mine = load_seq_t<false>(p, tid, &bad);
+      int T_, I_; seq_shape(p, s_mine, ROWS_WG, T_, I_);
+      vt = T_ * I_;
+    }
+    const int it = wave_incl_scan(vt, lane);
+    if (lane == 63) sh_w[wave] = it;
     if (tid == 0) sh_found[0] = -1;
     __syncthreads();
+    int wt = 0;
+#pragma unroll
+    for (int q = 0; q < MF_BLOCK / 64; ++q) {
+      if (q < wave) wt += sh_w[q];
+      total += (unsigned)sh_w[q];
+    }
+    total = __builtin_amdgcn_readfirstlane(total);
+    if (total == 0) return;
+    plan_shares();
+    if (w >= W_eff) return;
+    g0 = share_start(w); g1 = share_start(w + 1);
+    if (g1 <= g0) return;
+    const unsigned lo = (unsigned)(wt + it - vt), hi = (unsigned)(wt + it);
+    if (lo <= g0 && g0 < hi) {
+      sh_found[0] = tid; sh_found[1] = (int)lo;
+      sh_found[2] = s_mine.L; sh_found[3] = s_mine.row0; sh_found[4] = s_mine.n; sh_found[5] = s_mine.k;
+      sh_found[6] = s_mine.v; sh_found[7] = s_mine.page0; sh_found[8] = s_mine.npages;
+    }
+    if (bad) flag_status(p.status, bad);
+    __syncthreads();
+    seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
+    if (seq < 0) return;                                         // cannot happen for consistent data
+    Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
+    ws.L = __builtin_amdgcn_readfirstlane(sh_found[2]);      ws.row0 = __builtin_amdgcn_readfirstlane(sh_found[3]);
+    ws.n = __builtin_amdgcn_readfirstlane(sh_found[4]);      ws.k = __builtin_amdgcn_readfirstlane(sh_found[5]);
+    ws.v = __builtin_amdgcn_readfirstlane(sh_found[6]);      ws.page0 = __builtin_amdgcn_readfirstlane(sh_found[7]);
+    ws.npages = __builtin_amdgcn_readfirstlane(sh_found[8]);
+  } else {
+    // larger batches: a first pass for the total, a second, block by block, for the owner of g0
+    int part = 0;
+    for (int i = tid; i < p.B; i += MF_BLOCK) {
+      SeqInfo s = load_seq_t<false>(p, i);
+      int T_, I_; seq_shape(p, s, ROWS_WG, T_, I_);
+      part += T_ * I_;
+    }
+    part = wave_incl_scan(part, lane);
+    if (lane == 63) sh_w[wave] = part;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < MF_BLOCK / 64; ++q) total += (unsigned)sh_w[q];
+    total = __builtin_amdgcn_readfirstlane(total);
+    if (tid == 0) sh_found[0] = -1;
+    __syncthreads();
+    if (total == 0) return;
+    plan_shares();
+    if (w >= W_eff) return;
+    g0 = share_start(w); g1 = share_start(w + 1);
+    if (g1 <= g0) return;
+    unsigned base_t = 0;
     for (int blk = 0; blk < p.B; blk += MF_BLOCK) {
       const int i = blk + tid;
-      int T = 0, I = 0;
-      if (i < p.B) { SeqInfo s = load_seq_t<false>(p, i); seq_shape(p, s, ROWS_WG, T, I); }
-      const long long vt = (long long)T * I;
-      long long it = wave_incl_scan(vt, lane);
-      if (lane == 63) sh_ll[wave] = it;
+      int T_ = 0, I_ = 0;
+      if (i < p.B) { SeqInfo s = load_seq_t<false>(p, i); seq_shape(p, s, ROWS_WG, T_, I_); }
+      const int vt = T_ * I_;
+      const int it = wave_incl_scan(vt, lane);
+      if (lane == 63) sh_w[wave] = it;
       __syncthreads();
-      long long wt = 0, bt = 0;
+      unsigned wt = 0, bt = 0;
+#pragma unroll
       for (int q = 0; q < MF_BLOCK / 64; ++q) {
-        if (q < wave) wt += sh_ll[q];
-        bt += sh_ll[q];
+        if (q < wave) wt += (unsigned)sh_w[q];
+        bt += (unsigned)sh_w[q];
       }
-      const long long lo = base_t + wt + it - vt, hi = base_t + wt + it;
-      if (i < p.B && lo <= g0 && g0 < hi) {
-        sh_found[0] = i; sh_found[1] = (int)(lo & 0xffffffffll); sh_found[2] = (int)(lo >> 32);
-      }
+      const unsigned lo = base_t + wt + (unsigned)(it - vt), hi = base_t + wt + (unsigned)it;
+      if (i < p.B && lo <= g0 && g0 < hi) { sh_found[0] = i; sh_found[1] = (int)lo; }
       base_t += bt;
       __syncthreads();
       if (sh_found[0] >= 0) break;
     }
+    seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
+    if (seq < 0) return;                                         // cannot happen for consistent data
+    Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
   }
-  int seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
-  if (seq < 0) return;                                           // cannot happen for consistent data
-  long long Pt = uniform_ll(((long long)(unsigned)sh_found[1]) | ((long long)sh_found[2] << 32));   // tiles before seq
 
   const int ld_key = tid >> 4;                 // 0..15: key within a 16-key group
   const int ld_col = (tid & 15) * 8;           // element offset of this thread's 16 bytes
@@ -196,7 +247,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   };
   // ---- walk over the share, one piece (run of tiles inside one item) at a time ----------------
   // The walk state (sequence, its shape, tiles before it) only moves forward.
-  SeqInfo ws = get_seq(seq);
+  if (p.B > MF_BLOCK) ws = get_seq(seq);
   int T, I; seq_shape(p, ws, ROWS_WG, T, I);
 
   struct Piece {
@@ -206,28 +257,28 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     int n_ct_all;               // cached tiles of the item (the rest are tiles of new rows)
     long long head_off;         // head * cache_stride_head
     const int* pi;              // the sequence's page list
-    long long item_a;           // global index of the item's first tile
+    unsigned item_a;            // global index of the item's first tile
   };
   // descriptor of the piece that starts at global tile g (g < g1); false if the data ran out
-  auto make_piece = [&](long long g, Piece& pc) -> bool {
-    while (g >= Pt + (long long)T * I) {
-      Pt += (long long)T * I;
+  auto make_piece = [&](unsigned g, Piece& pc) -> bool {
+    while (g >= Pt + (unsigned)(T * I)) {
+      Pt += (unsigned)(T * I);
       ++seq;
       if (seq >= p.B) return false;
       ws = get_seq(seq);
       seq_shape(p, ws, ROWS_WG, T, I);
     }
-    const long long local = g - Pt;
-    const int item = (int)(local / T);
+    const int local = (int)(g - Pt);
+    const int item = local / T;
     const int RT = I / p.Hkv;
     pc.s = ws; pc.seq = seq; pc.T = T;
     pc.head = item / RT; pc.rt = item - pc.head * RT;
-    pc.tile0 = (int)(local - (long long)item * T);
-    pc.nt = (int)min((long long)(T - pc.tile0), g1 - g);
+    pc.tile0 = local - item * T;
+    pc.nt = min(T - pc.tile0, (int)(g1 - g));
     pc.n_ct_all = (ws.L + MF_TK - 1) / MF_TK;
     pc.head_off = (long long)pc.head * p.sh;
     pc.pi = p.page_indices + ws.page0;
-    pc.item_a = Pt + (long long)item * T;
+    pc.item_a = Pt + (unsigned)(item * T);
     return true;
   };
 
@@ -239,18 +290,12 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // fetched with scalar loads ahead of time and range-checked when the addresses are formed.
   auto fetch_pages = [&](const Piece& pc, int tau, int (&pg)[MF_GROUPS]) {
     if (tau < pc.n_ct_all) {
-      const int base = tau * MF_TK;
-      if (base + MF_TK <= pc.s.L) {
+      // groups past the end of the prefix re-read its last page id (unused): no branch, so the
+      // scalar loads of a tile go out back to back
+      const int base = tau * MF_TK, last = pc.s.L - 1;
 #pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j)
-          pg[j] = sload(pc.pi, __builtin_amdgcn_readfirstlane((base + 16 * j) >> sc_.page_shift));
-      } else {
-#pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j) {
-          int gs = base + 16 * j;
-          pg[j] = gs < pc.s.L ? sload(pc.pi, __builtin_amdgcn_readfirstlane(gs >> sc_.page_shift)) : 0;
-        }
-      }
+      for (int j = 0; j < MF_GROUPS; ++j)
+        pg[j] = sload(pc.pi, __builtin_amdgcn_readfirstlane(min(base + 16 * j, last) >> sc_.page_shift));
     }
   };
   // One 16-key group = 16 rows of 256 B at a fixed pitch from a base that is the same for the
@@ -328,11 +373,16 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
   for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
   TileRegs rA, rB;
-  // Everything a piece needs from memory before its first tile can be multiplied: page ids, the
-  // first two tiles (into rA, rB) and this lane's query row.  Issued as early as possible - for
-  // every piece but the first, while the previous piece is still being merged and stored.
-  auto start_piece = [&](const Piece& pc, const Lane& ln) {
-    fetch_pages(pc, pc.tile0, pg);
+  // What a piece needs from memory before its first tile can be multiplied comes in two steps:
+  // the page ids of its first two tiles (scalar loads), then, with those, the two tiles (into
+  // rA, rB) and this lane's query row.  For every piece but the first, the ids are requested
+  // before the previous piece's tile loop and the data before the previous piece is merged and
+  // stored, so neither latency is exposed.
+  auto start_ids = [&](const Piece& pc, int (&id0)[MF_GROUPS], int (&id1)[MF_GROUPS]) {
+    fetch_pages(pc, pc.tile0, id0);
+    if (pc.nt > 1) fetch_pages(pc, pc.tile0 + 1, id1);
+  };
+  auto start_loads = [&](const Piece& pc, const Lane& ln, const int (&id0)[MF_GROUPS], const int (&id1)[MF_GROUPS]) {
     const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(pc.s.row0 + (ln.row_valid ? ln.nn : 0)) * p.Hq + ln.hq) * MF_D + 8 * h;
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
@@ -340,23 +390,28 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       if (ln.row_valid) wq = *reinterpret_cast<const u32x4*>(qp + 16 * st);
       qf[st] = as_bf16x8(wq);
     }
-    load_tile(pc, pc.tile0, pg, rA);
-    if (pc.nt > 1 && DBG != 2) {
-      fetch_pages(pc, pc.tile0 + 1, pg);
-      load_tile(pc, pc.tile0 + 1, pg, rB);
-    }
+    load_tile(pc, pc.tile0, id0, rA);
+    if (pc.nt > 1 && DBG != 2) load_tile(pc, pc.tile0 + 1, id1, rB);
     fetch_pages(pc, pc.tile0 + 2, pg);
   };
 
-  long long g = g0;
+  unsigned g = g0;
   bool first_piece = true;
   Piece cur;
   if (!make_piece(g, cur)) return;
   Lane ln = make_lane(cur);
-  start_piece(cur, ln);
+  int nid0[MF_GROUPS], nid1[MF_GROUPS];
+#pragma unroll
+  for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
+  start_ids(cur, nid0, nid1);
+  start_loads(cur, ln, nid0, nid1);
   FD_TL(tl1);
   bool have = true;
   while (have) {
+    // descriptor and page ids of the piece after this one: in flight during the tile loop
+    Piece nxt;
+    have = (g + (unsigned)cur.nt < g1) && make_piece(g + (unsigned)cur.nt, nxt);
+    if (have) start_ids(nxt, nid0, nid1);
     const SeqInfo& s = cur.s;
     const int tile0 = cur.tile0, nt = cur.nt, n_ct_all = cur.n_ct_all, c1 = cur.s.L;
     const bool whole = (tile0 == 0) && (nt == cur.T);
@@ -365,11 +420,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       // this item started in an earlier work-group and ends here: leave it to the combine kernel.
       // Its first piece sits in the work-group wf that owns the item's first tile, in slot 2 wf
       // if the item begins exactly at wf's share, else 2 wf + 1; later pieces are in slots 2 w'.
-      const long long a = cur.item_a;
-      int wf = (int)(a * W_eff / total);
-      while ((long long)(wf + 1) * total / W_eff <= a) ++wf;
-      while ((long long)wf * total / W_eff > a) --wf;
-      const int first_slot = 2 * wf + (((long long)wf * total / W_eff == a) ? 0 : 1);
+      const unsigned a = cur.item_a;
+      int wf = min((int)(a / max(sh_q, 1u)), w);
+      while (wf + 1 <= w && share_start(wf + 1) <= a) ++wf;
+      while (wf > 0 && share_start(wf) > a) --wf;
+      const int first_slot = 2 * wf + (share_start(wf) == a ? 0 : 1);
       sc_.entries[w] = make_int4(cur.seq, cur.head, cur.rt, first_slot);
     }
     const int RB = ln.RB, KQ = ln.KQ, rb = ln.rb, kq = ln.kq, trow = ln.trow, nn = ln.nn, hq = ln.hq;
@@ -389,6 +444,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (first_piece) FD_TL(tl2);
     ++tl_pieces;
 #endif
+    FD_TLP(0);                                     // first tile of the piece is in LDS
 
     // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
     // (requested earlier) is written to the other LDS buffer and tile t+2 is requested.
@@ -498,12 +554,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       if (t + 1 < nt) iteration(t + 1, rA, rB);
     }
 
+    FD_TLP(1);                                     // tiles done
     // ---- next piece: get its loads going before this one is merged and stored --------------
-    g += nt;
-    Piece nxt; Lane ln_next = ln;
-    have = (g < g1) && make_piece(g, nxt);
-    if (have) { ln_next = make_lane(nxt); start_piece(nxt, ln_next); }
+    g += (unsigned)nt;
+    Lane ln_next = ln;
+    if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1); }
 
+    FD_TLP(2);                                     // next piece requested
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
     float* xch = reinterpret_cast<float*>(lds);                    // [wave][66][64] floats
     if (MAXRB != 4 && KQ > 1) {
@@ -565,6 +622,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       }
     }
     __syncthreads();                              // LDS is reused by the next piece
+    FD_TLP(3);                                     // merged and stored
     first_piece = false;
     if (have) { cur = nxt; ln = ln_next; }
   }
@@ -573,6 +631,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   if (p.tl && tid == 0) {
     unsigned long long* o8 = p.tl + (size_t)w * 8;
     o8[0] = tl0; o8[1] = tl1; o8[2] = tl2; o8[3] = tl3; o8[4] = (unsigned long long)(g1 - g0); o8[5] = tl_pieces;
+    o8[6] = __builtin_amdgcn_s_getreg(63492); o8[7] = __builtin_amdgcn_s_getreg(63508);
   }
 #endif
 }

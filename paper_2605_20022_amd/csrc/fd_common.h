@@ -84,9 +84,10 @@ struct AttnParams {
 
 // SCALAR: read through the scalar path (index uniform across the wave) and report bad data
 // through the status word; otherwise plain per-lane loads and no reporting (used when lanes
-// scan different sequences).  Both give identical clamped values.
+// scan different sequences; `bad_out` then receives the FD_DEV_* bits).  Both give identical
+// clamped values.
 template <bool SCALAR>
-__device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i) {
+__device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i, uint32_t* bad_out = nullptr) {
   auto ld = [&](const int* a, int idx) { return SCALAR ? sload(a, idx) : a[idx]; };
   SeqInfo s;
   int L = ld(p.kv_len, i);
@@ -117,6 +118,7 @@ __device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i) {
     s.L = s.npages * p.page_size < s.L ? s.npages * p.page_size : s.L;
   }
   if (SCALAR && bad) flag_status(p.status, bad);
+  if (bad_out) *bad_out = bad;
   return s;
 }
 

@@ -66,6 +66,7 @@ def test_generic_kernel_small_cases(fd, case, dtype):
     dict(B=2, G=8, Hkv=1, ps=64, kv=(100, 700), kr=(16, 16), m=16),        # 256 tile rows: two row tiles
     dict(B=3, G=2, Hkv=2, ps=16, kv=(200, 900), kr=(1, 40), m=40),         # > 64 new rows: two new-row tiles
     dict(B=5, G=4, Hkv=2, ps=16, kv=(1, 130), kr=(1, 16), m=0),            # sequential mode, ragged k
+    dict(B=300, G=4, Hkv=1, ps=16, kv=(0, 150), kr=(0, 3), m=2),           # batch larger than one work-group's scan block
 ])
 def test_mfma_kernel_small_cases(fd, case):
     w = _wl("small", "bf16", case["B"], case["G"] * case["Hkv"], case["Hkv"], 128, case["ps"], case["kv"],
