@@ -199,7 +199,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(sequences, KV heads or KV ranges would shard it; see DESIGN.md).", file=sys.stderr)
+              "(sequences, KV heads or KV ranges would shard it).", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -60,7 +60,7 @@ struct MfmaSched {
   int fixed_share;    // > 0: tiles per work-group asked for by the caller
   float* part_acc;    // [2 * num_wgs][ROWS_WG][D]
   float* part_ml;     // [2 * num_wgs][ROWS_WG][2]
-  int4* entries;      // [num_wgs]: the split item that ends in this work-group: (seq, head, row block, first slot); seq < 0: none
+  int4* entries;      // [num_wgs]: the split item that ends in this work-group: (first packed row, head | row block << 16, tile rows, first slot); first < 0: none
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       while (wf + 1 <= w && share_start(wf + 1) <= a) ++wf;
       while (wf > 0 && share_start(wf) > a) --wf;
       const int first_slot = 2 * wf + (share_start(wf) == a ? 0 : 1);
-      sc_.entries[w] = make_int4(cur.seq, cur.head, cur.rt, first_slot);
+      sc_.entries[w] = make_int4(cur.s.row0, cur.head | (cur.rt << 16), min(ROWS_WG, cur.s.n * p.G - cur.rt * ROWS_WG), first_slot);
     }
     const int RB = ln.RB, KQ = ln.KQ, rb = ln.rb, kq = ln.kq, trow = ln.trow, nn = ln.nn, hq = ln.hq;
     const bool row_valid = ln.row_valid, wave_has_rows = ln.wave_has_rows;
@@ -640,40 +640,85 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 // Merge the split partials of every item that was cut by a share boundary:
 //   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
 // The pieces of an item sit in its first slot, then in the first slot (2w) of every later
-// work-group up to the one it ended in.  grid (num_wgs, ROWS_WG / 2), 256 threads = 2 rows x 128.
+// work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 4):
+// one wave per tile row, a lane owns two adjacent output columns.
 // ---------------------------------------------------------------------------------------
 template <int MAXRB>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
   const int wl = blockIdx.x;                      // the work-group in which the split item ended
-  const int4 en = sc_.entries[wl];
-  const int seq = en.x, head = en.y, rt = en.z, first_slot = en.w;
-  if (seq < 0 || seq >= p.B) return;
-  const SeqInfo s = load_seq(p, seq);
-  const int rows_total = s.n * p.G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int* ep = reinterpret_cast<const int*>(sc_.entries + wl);
+  const int row0 = sload(ep, 0), head_rt = sload(ep, 1), rows_here = sload(ep, 2), first_slot = sload(ep, 3);
+  if (row0 < 0) return;
+  const int trow = blockIdx.y * 4 + wave;
+  const int head = head_rt & 0xffff, rt = head_rt >> 16;
   const int wf = first_slot >> 1;
-  if (s.n <= 0 || rt < 0 || rt * ROWS_WG >= rows_total || head < 0 || head >= p.Hkv || first_slot < 0 || wf >= wl) return;
-  const int rows_here = min(ROWS_WG, rows_total - rt * ROWS_WG);
-  bf16_t* out = reinterpret_cast<bf16_t*>(p.out);
-  // two tile rows per work-group: thread -> (row, d)
-  const int trow = 2 * blockIdx.y + (threadIdx.x >> 7), d = threadIdx.x & 127;
-  if (trow >= rows_here) return;
-  float M = sc_.part_ml[((long long)first_slot * ROWS_WG + trow) * 2];
-  for (int ww = wf + 1; ww <= wl; ++ww) M = fmaxf(M, sc_.part_ml[((long long)(2 * ww) * ROWS_WG + trow) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int ww = wf; ww <= wl; ++ww) {
-    const long long ps = (long long)(ww == wf ? first_slot : 2 * ww) * ROWS_WG + trow;
-    const float mc = sc_.part_ml[ps * 2];
-    if (mc == -INFINITY) continue;
-    const float wgt = exp2f(mc - M);
-    num = fmaf(wgt, sc_.part_acc[ps * MF_D + d], num);
-    den = fmaf(wgt, sc_.part_ml[ps * 2 + 1], den);
-  }
+  if (trow >= rows_here || rows_here > ROWS_WG || first_slot < 0 || wf >= wl || head >= p.Hkv) return;
   const int T_row = rt * ROWS_WG + trow;
   const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
-  const long long orow = (long long)(s.row0 + nn) * p.Hq + hq;
-  out[orow * MF_D + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-  if (p.lse && d == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
+  if (row0 + nn >= p.total_rows) return;
+  const int np = wl - wf + 1;                     // pieces: slot first_slot, then 2 (wf + 1) .. 2 wl
+  auto ml_of = [&](int pi) -> const float* {
+    const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
+    return sc_.part_ml + (slot * ROWS_WG + trow) * 2;
+  };
+  auto acc_of = [&](int pi) -> const f32x2* {
+    const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
+    return reinterpret_cast<const f32x2*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + lane;
+  };
+  f32x2 num = {0.f, 0.f};
+  float den = 0.f, M = -INFINITY;
+  if (np <= 4) {
+    // the usual case: everything is requested at once, one memory latency
+    float mc[4], lc[4]; f32x2 a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int pu = min(u, np - 1);
+      const float* ml = ml_of(pu);
+      mc[u] = u < np ? ml[0] : -INFINITY; lc[u] = ml[1]; a[u] = *acc_of(pu);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) M = fmaxf(M, mc[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wgt = mc[u] == -INFINITY ? 0.f : exp2f(mc[u] - M);
+      num[0] = fmaf(wgt, a[u][0], num[0]); num[1] = fmaf(wgt, a[u][1], num[1]);
+      den = fmaf(wgt, lc[u], den);
+    }
+  } else {
+    // many pieces (a long item spread over many work-groups): maxima one piece per lane, then
+    // the partials four at a time
+    for (int p0 = 0; p0 < np; p0 += 64)
+      if (p0 + lane < np) M = fmaxf(M, ml_of(p0 + lane)[0]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    int pi = 0;
+    for (; pi + 4 <= np; pi += 4) {
+      float mc[4], lc[4]; f32x2 a[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { const float* ml = ml_of(pi + u); mc[u] = ml[0]; lc[u] = ml[1]; a[u] = *acc_of(pi + u); }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float wgt = mc[u] == -INFINITY ? 0.f : exp2f(mc[u] - M);
+        num[0] = fmaf(wgt, a[u][0], num[0]); num[1] = fmaf(wgt, a[u][1], num[1]);
+        den = fmaf(wgt, lc[u], den);
+      }
+    }
+    for (; pi < np; ++pi) {
+      const float* ml = ml_of(pi);
+      const float mc = ml[0], lc = ml[1];
+      const f32x2 a = *acc_of(pi);
+      const float wgt = mc == -INFINITY ? 0.f : exp2f(mc - M);
+      num[0] = fmaf(wgt, a[0], num[0]); num[1] = fmaf(wgt, a[1], num[1]);
+      den = fmaf(wgt, lc, den);
+    }
+  }
+  const float inv = den > 0.f ? 1.0f / den : 0.f;
+  const long long orow = (long long)(row0 + nn) * p.Hq + hq;
+  reinterpret_cast<unsigned*>(reinterpret_cast<bf16_t*>(p.out) + orow * MF_D)[lane] = pack_bf16x2(num[0] * inv, num[1] * inv);
+  if (p.lse && lane == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -754,7 +799,7 @@ hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, 0, sc, rows_wg);
-  dim3 grid(sc.num_wgs, rows_wg / 2);
+  dim3 grid(sc.num_wgs, rows_wg / 4);
   if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
   else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
   return hipGetLastError();
