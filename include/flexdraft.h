@@ -108,7 +108,9 @@ typedef struct fd_attn_args {
   int32_t max_kv_len;         /* >= every kv_len[i]                                           */
   int32_t max_new_rows;       /* >= every n_i                                                 */
   int32_t num_pages;          /* physical pages in the pool; page ids are checked against it  */
-  int32_t kv_chunk;           /* cached tokens per work-group, multiple of 128; 0 => automatic */
+  int32_t kv_chunk;           /* 0 => automatic.  > 0 (multiple of 64): keys of work handed to
+                               * one work-group - the chunk of a sequence's prefix (fp32
+                               * kernel) or the share of the batch's key tiles (MFMA kernel) */
   int32_t reserved;
   const void *k_cache;        /* device                                                       */
   const void *v_cache;        /* device                                                       */

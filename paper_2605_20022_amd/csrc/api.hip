@@ -45,6 +45,17 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 hipEvent_t* g_prof_events = nullptr;
 int g_prof_cap = 0, g_prof_used = 0;
 
+// Builds with -DFD_MEASURE carry two timing-only variants of the MFMA kernel (selected by bits
+// 8-9 of flags; their output is meaningless); the product build has neither.
+inline int measure_variant(int flags) {
+#ifdef FD_MEASURE
+  return (flags >> 8) & 3;
+#else
+  (void)flags;
+  return 0;
+#endif
+}
+
 struct AttnPlan {
   bool use_mfma;
   int chunk, max_chunks, row_tiles;
@@ -175,7 +186,7 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   const bool prof = g_prof_events && g_prof_used < g_prof_cap;
   if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
     return fail(FD_ERR_HIP, "hipEventRecord failed");
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, (a->flags >> 8) & 3, stream)
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, measure_variant(a->flags), stream)
                                : fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
   if (prof) {

@@ -6,15 +6,20 @@
 // cached keys followed by the tile(s) of the sequence's own new rows.  All tiles of all
 // items, in (sequence, head, row block) order, form one line of work that is cut into equal
 // shares, one per persistent work-group (two work-groups per CU), so that every CU streams
-// the same number of bytes whatever the length mix of the batch.  A work-group that owns a
-// whole item normalises and stores it; an item cut by a share boundary leaves one split
-// partial (base-2 running max, sum, un-normalised O) per work-group that touched it, merged
-// by the combine kernel below.
+// the same number of bytes whatever the length mix of the batch.  A share is walked as a
+// sequence of *pieces* (runs of tiles inside one item).  A piece that covers a whole item is
+// normalised and stored; an item cut by a share boundary leaves one split partial (base-2
+// running max, sum, un-normalised O) per work-group that touched it, and the work-group in
+// which it ends leaves an entry for the combine kernel below.
 //
 // Streaming of one tile by the four waves of a work-group:
-//   global --16-byte coalesced loads, one 4 KB page slab per instruction--> registers
-//          (the next tile is in flight while the current one is multiplied)
-//          --> LDS, double buffered, K rows padded to 272 B, V rows to 288 B, one barrier/tile
+//   page ids           scalar loads, one tile ahead (they are uniform across the work-group)
+//   global -> regs     one 16-key group (a 4 KB K slab and a 4 KB V slab of one page) per
+//                      buffer_load_dwordx4, through a buffer descriptor built in scalar
+//                      registers: no per-lane address arithmetic, and rows past the end of the
+//                      prefix lie outside the descriptor and read as zero.  Two tiles are in
+//                      flight in registers while a third is multiplied.
+//   regs -> LDS        double buffered, K rows padded to 272 B, V rows to 288 B, one barrier/tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS (ds_read_b128),
 //                      B = Q fragments held in registers for the whole item
 //   online softmax     in the accumulator layout: a lane owns ONE query row (column of
@@ -22,11 +27,13 @@
 //                      with lane^32 and the row sum none until the end
 //   O^T += V^T P^T     A = V^T fragments fetched with ds_read_b64_tr_b16 (the LDS transpose
 //                      read of gfx950), B = P packed to bf16 straight from the S^T registers
+// The next piece's page ids are requested before the current piece's tile loop, its first two
+// tiles and query rows before the current piece is merged and stored.
 //
-// The tile rows in use form RB = 1, 2 or 4 blocks of 32; wave w takes row block w % RB and,
-// of each tile's two 32-key blocks, the one with index w / RB (both when RB = 4).  With few
-// rows the waves split the keys, with many rows they split the rows; waves that shared a row
-// block merge their running (max, sum, O) through LDS at the end of the piece.
+// Wave roles.  64-row variant: the tile rows in use form RB = 1 or 2 blocks of 32; wave w takes
+// row block w % RB and, of each tile's two 32-key blocks, the one with index w / RB; waves that
+// shared a row block merge their running (max, sum, O) through LDS at the end of the piece.
+// 128-row variant: wave w owns row block w and every key block, no merge.
 //
 // The cached prefix is unmasked (every new row sees all of it, Sec. 4.1); only the ragged
 // last tile and the tile of new rows apply the visibility rule, in registers.
@@ -101,7 +108,7 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
-// DBG (measurement builds only): 1 = stream tiles but skip the arithmetic, 2 = do the arithmetic on
+// DBG (builds with -DFD_MEASURE only): 1 = stream tiles but skip the arithmetic, 2 = do the arithmetic on
 // whatever the first tile left in LDS and skip the global loads; both produce meaningless output.
 // MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
 template <int DBG, int MAXRB>
@@ -791,8 +798,12 @@ hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, kv_chunk, sc, rows_wg);
   const bool small = rows_wg == 64;
+#ifdef FD_MEASURE
   if (dbg == 1) return small ? launch_mfma<1, 2>(p, sc, st) : launch_mfma<1, 4>(p, sc, st);
   if (dbg == 2) return small ? launch_mfma<2, 2>(p, sc, st) : launch_mfma<2, 4>(p, sc, st);
+#else
+  (void)dbg;
+#endif
   return small ? launch_mfma<0, 2>(p, sc, st) : launch_mfma<0, 4>(p, sc, st);
 }
 
