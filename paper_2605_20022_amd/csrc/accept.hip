@@ -53,7 +53,15 @@ __device__ __forceinline__ void amax_merge(float& v, int& i, float ov, int oi) {
 // ---------------------------------------------------------------------------------------
 // Greedy, pass 1: arg-max of one vocabulary segment of one row.
 //   grid (segments, rows); part_val/part_idx [rows][segments]
+// A segment is at most ACC_BLOCK * 8 * ARG_ROUNDS logits, so a lane holds all of its share in
+// registers.  First the segment's maximum (one max per logit), then only the lanes whose own
+// maximum equals it look for the lowest index holding that value: comparing (value, index)
+// pairs logit by logit would cost several times the instructions and bound the kernel by
+// arithmetic rather than by the stream.
 // ---------------------------------------------------------------------------------------
+constexpr int ARG_ROUNDS = 5;
+constexpr int ARG_SEG_MAX = ACC_BLOCK * 8 * ARG_ROUNDS;
+
 template <typename T>
 __global__ __launch_bounds__(ACC_BLOCK) void argmax_partial_kernel(
     const T* __restrict__ logits, long long row_stride, int vocab, int seg_len,
@@ -62,26 +70,42 @@ __global__ __launch_bounds__(ACC_BLOCK) void argmax_partial_kernel(
   const T* rp = logits + (long long)row * row_stride;
   const bool vec_ok = (reinterpret_cast<uintptr_t>(rp) & 15) == 0;
   const int e0 = seg * seg_len;
-  const int e1 = min(vocab, e0 + seg_len);
-  float bv = -INFINITY; int bi = 0x7fffffff;
-  for (int e = e0 + threadIdx.x * 8; e < e1; e += ACC_BLOCK * 8) {
-    float x[8];
-    load8<T>(rp, e, e1, vec_ok, x);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      if (e + i < e1) amax_merge(bv, bi, x[i], e + i);
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    float ov = __shfl_xor(bv, off); int oi = __shfl_xor(bi, off);
-    amax_merge(bv, bi, ov, oi);
-  }
+  const int e1 = min(vocab, e0 + min(seg_len, ARG_SEG_MAX));
   __shared__ float sv[ACC_BLOCK / FD_WAVE]; __shared__ int si[ACC_BLOCK / FD_WAVE];
-  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+  float x[ARG_ROUNDS][8];
+#pragma unroll
+  for (int u = 0; u < ARG_ROUNDS; ++u) load8<T>(rp, e0 + (u * ACC_BLOCK + threadIdx.x) * 8, e1, vec_ok, x[u]);   // -inf past e1
+  float m = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < ARG_ROUNDS; ++u)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(m, x[u][i]);
+  float wm = m;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+  if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = wm;
+  __syncthreads();
+  float M = sv[0];
+#pragma unroll
+  for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) M = fmaxf(M, sv[w]);
+  int bi = 0x7fffffff;
+  if (m == M) {
+#pragma unroll
+    for (int u = ARG_ROUNDS - 1; u >= 0; --u)
+#pragma unroll
+      for (int i = 7; i >= 0; --i) {
+        const int idx = e0 + (u * ACC_BLOCK + threadIdx.x) * 8 + i;
+        if (x[u][i] == M && idx < e1) bi = idx;            // descending walk: the lowest index is kept
+      }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) bi = min(bi, __shfl_xor(bi, off));
+  if ((threadIdx.x & 63) == 0) si[threadIdx.x >> 6] = bi;
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) amax_merge(bv, bi, sv[w], si[w]);
-    part_val[(long long)row * nseg + seg] = bv;
+#pragma unroll
+    for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) bi = min(bi, si[w]);
+    part_val[(long long)row * nseg + seg] = M;
     part_idx[(long long)row * nseg + seg] = bi;
   }
 }
@@ -152,6 +176,19 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// e^y for y <= 0.  e^y = 2^(y log2 e): the product is formed in two pieces, so that its rounding
+// error (which grows with |y|) and the low part of log2 e enter as a first-order correction of
+// the hardware exp2 (good to 1 ulp).  About a third of the instructions of the library expf,
+// which is what the streaming passes below were spending their time on.
+__device__ __forceinline__ float exp_neg(float y) {
+  y = fmaxf(y, -104.f);                               // e^-104 is below the smallest normal float
+  const float t = y * 1.44269502e+00f;
+  float r = fmaf(y, 1.44269502e+00f, -t);             // rounding error of t, exactly
+  r = fmaf(y, 1.92596299e-08f, r);                    // log2 e = 1.44269502 + 1.92596299e-8
+  const float e = __builtin_amdgcn_exp2f(t);
+  return fmaf(e, r * 0.693147182f, e);
+}
+
 // One streaming pass with a running maximum: (m, s) with s = sum exp(x*invT - m), rescaled
 // whenever the maximum grows; thread results are merged the same way.
 template <typename T>
@@ -163,16 +200,16 @@ __device__ __forceinline__ void segment_max_sum(const T* rp, int e0, int e1, flo
     float m8 = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { x[i] *= inv_t; m8 = fmaxf(m8, x[i]); }   // padding stays -inf (invT > 0)
-    if (m8 > m) { s *= (double)expf(m - m8); m = m8; }
+    if (m8 > m) { s *= (double)exp_neg(m - m8); m = m8; }
     if (m > -INFINITY) {
       float part = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) part += expf(x[i] - m);
+      for (int i = 0; i < 8; ++i) part += exp_neg(x[i] - m);
       s += (double)part;
     }
   }
   const float wm = wave_max(m);
-  double ws = (m > -INFINITY) ? s * exp((double)m - (double)wm) : 0.0;
+  double ws = (m > -INFINITY) ? s * (double)exp_neg(m - wm) : 0.0;
   ws = wave_sum(ws);
   if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = wm; d_red[threadIdx.x >> 6] = ws; }
   __syncthreads();
@@ -180,7 +217,7 @@ __device__ __forceinline__ void segment_max_sum(const T* rp, int e0, int e1, flo
   for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) bm = fmaxf(bm, s_red[w]);
   double bs = 0.0;
   for (int w = 0; w < ACC_BLOCK / FD_WAVE; ++w)
-    if (s_red[w] > -INFINITY) bs += d_red[w] * exp((double)s_red[w] - (double)bm);
+    if (s_red[w] > -INFINITY) bs += d_red[w] * (double)exp_neg(s_red[w] - bm);
   __syncthreads();
   out_max = (double)bm; out_sum = bs;
 }
@@ -214,7 +251,7 @@ __device__ __forceinline__ void merge_row_stats(const double* part_row, int nseg
   double z = 0.0;
   for (int s = lane; s < nseg; s += FD_WAVE) {
     double ms = part_row[s * 4 + which], ss = part_row[s * 4 + which + 1];
-    if (ss > 0.0) z += ss * exp(ms - m);
+    if (ss > 0.0) z += ss * (double)exp_neg((float)(ms - m));      // maxima are floats held in doubles: the difference is exact
   }
   z = wave_sum(z);
   M = m; Z = z;
@@ -428,12 +465,15 @@ __global__ __launch_bounds__(ACC_BLOCK) void accept_sample_pick_kernel(
 // host-side launchers (called from api.hip)
 // ---------------------------------------------------------------------------------------
 static inline int pick_segments(int rows, int vocab) {
-  // enough work-groups to cover the chip a few times, but at least 4096 logits per group
+  // enough work-groups to cover the chip a few times, but at least 4096 logits per group, and
+  // never more logits per group than the arg-max pass holds in registers
   int want = (2048 + rows - 1) / (rows > 0 ? rows : 1);
   int cap = (vocab + 4095) / 4096;
   int s = want < 1 ? 1 : want;
   if (s > cap) s = cap;
   if (s > 64) s = 64;
+  int need = (vocab + ARG_SEG_MAX - 1) / ARG_SEG_MAX;
+  if (s < need) s = need;
   if (s < 1) s = 1;
   return s;
 }
