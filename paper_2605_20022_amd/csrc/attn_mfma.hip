@@ -124,9 +124,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #define FD_TL(x) x = wall_clock64()
   // stamp k (0..3) of piece tl_pieces-1 (first four pieces): written straight to memory by thread 0
 #define FD_TLP(k) do { if (p.tl && tid == 0 && tl_pieces >= 1 && tl_pieces <= 4) p.tl[8 * 1024 + (size_t)w * 16 + 4 * (tl_pieces - 1) + (k)] = wall_clock64(); } while (0)
+#define FD_TLS(k) do { if (p.tl && tid == 0) p.tl[8 * 1024 + (size_t)blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
 #else
 #define FD_TL(x)
 #define FD_TLP(k)
+#define FD_TLS(k)
 #endif
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
@@ -165,6 +167,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (lane == 63) sh_w[wave] = it;
     if (tid == 0) sh_found[0] = -1;
     __syncthreads();
+    FD_TLS(12);                                    // sequence arrays arrived, scanned
     int wt = 0;
 #pragma unroll
     for (int q = 0; q < MF_BLOCK / 64; ++q) {
@@ -185,6 +188,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     }
     if (bad) flag_status(p.status, bad);
     __syncthreads();
+    FD_TLS(13);                                    // starting sequence known
     seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
     if (seq < 0) return;                                         // cannot happen for consistent data
     Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
@@ -411,6 +415,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
   for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
   start_ids(cur, nid0, nid1);
+  FD_TLS(14);                                      // first page ids arrived (the stamp waits for them)
   start_loads(cur, ln, nid0, nid1);
   FD_TL(tl1);
   bool have = true;
