@@ -156,6 +156,9 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
       a->cache_stride_page % 8 || a->cache_stride_head % 8 || a->cache_stride_token % 8)
     return fail(FD_ERR_INVALID_ARG, "cache strides must be non-negative multiples of 8 elements, token stride >= head_dim");
   if (a->cache_stride_token > (1 << 24)) return fail(FD_ERR_UNSUPPORTED, "cache_stride_token above 2^24 elements");
+  if (plan.use_mfma && (a->cache_stride_page >= (1ll << 31) || a->cache_stride_head >= (1ll << 31) ||
+                        (long long)a->page_size * a->cache_stride_token >= (1ll << 31)))
+    return fail(FD_ERR_UNSUPPORTED, "cache strides of 2^31 elements or more");
   if (!a->workspace) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
   if (a->workspace_bytes < plan.total_bytes)
     return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", a->workspace_bytes, plan.total_bytes);

@@ -266,7 +266,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     int seq, head, rt;          // item
     int tile0, nt, T;           // tiles [tile0, tile0 + nt) of the item's T
     int n_ct_all;               // cached tiles of the item (the rest are tiles of new rows)
-    long long head_off;         // head * cache_stride_head
+    const bf16_t* kh;           // K cache and V cache advanced to the item's head
+    const bf16_t* vh;
     const int* pi;              // the sequence's page list
     unsigned item_a;            // global index of the item's first tile
   };
@@ -287,7 +288,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     pc.tile0 = local - item * T;
     pc.nt = min(T - pc.tile0, (int)(g1 - g));
     pc.n_ct_all = (ws.L + MF_TK - 1) / MF_TK;
-    pc.head_off = (long long)pc.head * p.sh;
+    pc.kh = Kc + (long long)pc.head * p.sh;
+    pc.vh = Vc + (long long)pc.head * p.sh;
     pc.pi = p.page_indices + ws.page0;
     pc.item_a = Pt + (unsigned)(item * T);
     return true;
@@ -301,38 +303,66 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // fetched with scalar loads ahead of time and range-checked when the addresses are formed.
   auto fetch_pages = [&](const Piece& pc, int tau, int (&pg)[MF_GROUPS]) {
     if (tau < pc.n_ct_all) {
-      // groups past the end of the prefix re-read its last page id (unused): no branch, so the
-      // scalar loads of a tile go out back to back
       const int base = tau * MF_TK, last = pc.s.L - 1;
+      if (sc_.page_shift == 4 && base + MF_TK - 1 <= last) {
+        // 16-token pages, full tile: four consecutive page ids, one scalar load
+        typedef int i32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));     // ids are only 4-byte aligned
+        typedef const __attribute__((address_space(4))) i32x4_a4* const_i32x4_ptr;
+        const int first = __builtin_amdgcn_readfirstlane(base >> 4);
+        const i32x4_a4 v4 = *(const_i32x4_ptr)(uintptr_t)(pc.pi + first);
+        pg[0] = v4[0]; pg[1] = v4[1]; pg[2] = v4[2]; pg[3] = v4[3];
+      } else {
+        // groups past the end of the prefix re-read its last page id (unused): no branch, so the
+        // scalar loads of a tile go out back to back
 #pragma unroll
-      for (int j = 0; j < MF_GROUPS; ++j)
-        pg[j] = sload(pc.pi, __builtin_amdgcn_readfirstlane(min(base + 16 * j, last) >> sc_.page_shift));
+        for (int j = 0; j < MF_GROUPS; ++j)
+          pg[j] = sload(pc.pi, __builtin_amdgcn_readfirstlane(min(base + 16 * j, last) >> sc_.page_shift));
+      }
     }
   };
   // One 16-key group = 16 rows of 256 B at a fixed pitch from a base that is the same for the
   // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
-  // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows at or past
-  // `valid` lie outside the descriptor, so the hardware returns zeros for them.
-  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int valid, long long pitch, unsigned lane_off,
-                       u32x4& rk, u32x4& rv) {
-    const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
-    const int nrec = v16 > 0 ? (int)(((long long)(v16 - 1) * pitch + MF_D) * 2) : 0;
+  // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows past the
+  // descriptor's size read as zero.  `nrec` = bytes from the base to the end of the last valid row.
+  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, unsigned lane_off, u32x4& rk, u32x4& rv) {
     __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
     __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
     rk = __builtin_amdgcn_raw_buffer_load_b128(rk_, lane_off, 0, 2);      // aux 2: streaming (nt)
     rv = __builtin_amdgcn_raw_buffer_load_b128(rv_, lane_off, 0, 2);
   };
+  auto nrec_of = [&](int valid, unsigned pitch) -> int {                 // valid rows of a 16-row group
+    const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
+    return v16 > 0 ? (int)(((unsigned)(v16 - 1) * pitch + MF_D) * 2u) : 0;
+  };
+  // strides as 32-bit values (the host checks the ranges): page id x page stride is then a
+  // 32 x 32 -> 64 bit product instead of a 64 x 64 one
+  const unsigned sp32 = (unsigned)p.sp, st32 = (unsigned)p.st;
+  const int nrec_full = (int)((15u * st32 + MF_D) * 2u);
   auto load_tile = [&](const Piece& pc, int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
     if (tau < pc.n_ct_all) {
       const int base = tau * MF_TK;
-      bool bad = false;
+      unsigned bad = 0;
+      if (base + MF_TK <= pc.s.L) {                 // every key of the tile is valid: the usual case
 #pragma unroll
-      for (int j = 0; j < MF_GROUPS; ++j) {
-        const int gs = base + 16 * j;
-        int ph = pg[j];
-        if ((unsigned)ph >= (unsigned)p.num_pages) { bad = bad | (gs < pc.s.L); ph = 0; }
-        const long long ub = (long long)ph * p.sp + (long long)(gs & page_mask) * p.st + pc.head_off;
-        load_rows(Kc + ub, Vc + ub, pc.s.L - gs, p.st, lane_boff, r.k[j], r.v[j]);
+        for (int j = 0; j < MF_GROUPS; ++j) {
+          unsigned ph = (unsigned)pg[j];
+          const unsigned oob = ph >= (unsigned)p.num_pages ? 1u : 0u;
+          bad |= oob;
+          ph = oob ? 0u : ph;
+          const unsigned long long ub = (unsigned long long)ph * sp32 + (unsigned)((base + 16 * j) & page_mask) * st32;
+          load_rows(pc.kh + ub, pc.vh + ub, nrec_full, lane_boff, r.k[j], r.v[j]);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < MF_GROUPS; ++j) {
+          const int gs = base + 16 * j;
+          unsigned ph = (unsigned)pg[j];
+          const unsigned oob = ph >= (unsigned)p.num_pages ? 1u : 0u;
+          bad |= oob & (gs < pc.s.L ? 1u : 0u);
+          ph = oob ? 0u : ph;
+          const unsigned long long ub = (unsigned long long)ph * sp32 + (unsigned)(gs & page_mask) * st32;
+          load_rows(pc.kh + ub, pc.vh + ub, nrec_of(pc.s.L - gs, st32), lane_boff, r.k[j], r.v[j]);
+        }
       }
       if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
     } else {
@@ -341,7 +371,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       for (int j = 0; j < MF_GROUPS; ++j) {
         const int key0 = base + 16 * j;
         const long long ub = ((long long)(pc.s.row0 + key0) * p.Hkv + pc.head) * MF_D;
-        load_rows(Kn + ub, Vn + ub, pc.s.n - key0, new_pitch, lane_off_new, r.k[j], r.v[j]);
+        load_rows(Kn + ub, Vn + ub, nrec_of(pc.s.n - key0, (unsigned)new_pitch), lane_off_new, r.k[j], r.v[j]);
       }
     }
   };
