@@ -8,7 +8,7 @@ the logits are rotated over enough device copies that no step finds its input in
 256 MB last-level cache.  One JSON line is printed; `value` is algorithmic KV-cache bytes
 per step divided by the step time.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--headline-only] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -192,7 +192,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--all-configs", action="store_true", help="also report every configuration in per_config")
+    ap.add_argument("--all-configs", dest="all_configs", action="store_true", default=True,
+                    help="also report every configuration in per_config (default)")
+    ap.add_argument("--headline-only", dest="all_configs", action="store_false",
+                    help="skip the per-configuration table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run the library's plain 1 GiB streaming copy (bandwidth yard-stick, counter calibration)")
