@@ -53,6 +53,7 @@ constexpr int MF_BUF_ELEMS = MF_K_ELEMS + MF_V_ELEMS;     // one K+V tile
 constexpr size_t MF_LDS_BYTES = (size_t)2 * MF_BUF_ELEMS * sizeof(bf16_t);   // double buffered
 constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
 constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
+constexpr int MF_START_COST = 2;          // what starting an item costs a work-group, in tile times
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -62,6 +63,7 @@ struct TileRegs { u32x4 k[MF_GROUPS]; u32x4 v[MF_GROUPS]; };
 // Launch-time scheduling parameters and the split-partial storage.
 struct MfmaSched {
   int page_shift;
+  int group_shift;    // log2(query heads per KV head), -1 if that is not a power of two
   int num_wgs;        // persistent work-groups launched
   int min_share;      // automatic shares are never smaller than this many tiles
   int fixed_share;    // > 0: tiles per work-group asked for by the caller
@@ -94,6 +96,13 @@ __device__ __forceinline__ void seq_shape(const AttnParams& p, const SeqInfo& s,
   tiles = (s.L + MF_TK - 1) / MF_TK + (s.n + MF_TK - 1) / MF_TK;
   items = p.Hkv * ((s.n * p.G + rows_wg - 1) / rows_wg);
 }
+
+// Work units of one item with `tiles` tiles.  The line of work is cut into shares of equal
+// *time*, not of equal tile count: beginning an item (new query rows, new page list, the merge
+// and the stores of the one before) costs about as much as streaming two tiles, so every item is
+// preceded by MF_START_COST units that stand for no tile.  A work-group whose share holds an
+// item boundary gets that many tiles less.
+__device__ __forceinline__ int item_units(int tiles) { return tiles > 0 ? tiles + MF_START_COST : 0; }
 
 // A 64-bit value known to be equal in every lane, moved to scalar registers.
 __device__ __forceinline__ long long uniform_ll(long long v) {
@@ -161,7 +170,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (tid < p.B) {
       s_mine = load_seq_t<false>(p, tid, &bad);
       int T_, I_; seq_shape(p, s_mine, ROWS_WG, T_, I_);
-      vt = T_ * I_;
+      vt = item_units(T_) * I_;
     }
     const int it = wave_incl_scan(vt, lane);
     if (lane == 63) sh_w[wave] = it;
@@ -202,7 +211,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     for (int i = tid; i < p.B; i += MF_BLOCK) {
       SeqInfo s = load_seq_t<false>(p, i);
       int T_, I_; seq_shape(p, s, ROWS_WG, T_, I_);
-      part += T_ * I_;
+      part += item_units(T_) * I_;
     }
     part = wave_incl_scan(part, lane);
     if (lane == 63) sh_w[wave] = part;
@@ -222,7 +231,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       const int i = blk + tid;
       int T_ = 0, I_ = 0;
       if (i < p.B) { SeqInfo s = load_seq_t<false>(p, i); seq_shape(p, s, ROWS_WG, T_, I_); }
-      const int vt = T_ * I_;
+      const int vt = item_units(T_) * I_;
       const int it = wave_incl_scan(vt, lane);
       if (lane == 63) sh_w[wave] = it;
       __syncthreads();
@@ -265,34 +274,49 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     SeqInfo s;                  // the sequence (scalar registers)
     int seq, head, rt;          // item
     int tile0, nt, T;           // tiles [tile0, tile0 + nt) of the item's T
+    int units;                  // units of the line the piece covers
     int n_ct_all;               // cached tiles of the item (the rest are tiles of new rows)
     const bf16_t* kh;           // K cache and V cache advanced to the item's head
     const bf16_t* vh;
     const int* pi;              // the sequence's page list
-    unsigned item_a;            // global index of the item's first tile
+    unsigned item_u;            // the item's first unit on the line
   };
-  // descriptor of the piece that starts at global tile g (g < g1); false if the data ran out
+  // descriptor of the piece that starts at unit g of the line (g < g1); false if the data ran out.
+  // A piece may hold no tile at all (its units are start-up units only): pc.nt == 0.
   auto make_piece = [&](unsigned g, Piece& pc) -> bool {
-    while (g >= Pt + (unsigned)(T * I)) {
-      Pt += (unsigned)(T * I);
+    while (g >= Pt + (unsigned)(item_units(T) * I)) {
+      Pt += (unsigned)(item_units(T) * I);
       ++seq;
       if (seq >= p.B) return false;
       ws = get_seq(seq);
       seq_shape(p, ws, ROWS_WG, T, I);
     }
+    const int Tu = item_units(T);
     const int local = (int)(g - Pt);
-    const int item = local / T;
+    const int item = local / Tu;
+    const int u = local - item * Tu;                               // unit within the item
+    const int ue = min(Tu, u + (int)min(g1 - g, 0x3fffffffu));     // end of the piece, in units
     const int RT = I / p.Hkv;
     pc.s = ws; pc.seq = seq; pc.T = T;
     pc.head = item / RT; pc.rt = item - pc.head * RT;
-    pc.tile0 = local - item * T;
-    pc.nt = min(T - pc.tile0, (int)(g1 - g));
+    pc.tile0 = max(u - MF_START_COST, 0);
+    pc.nt = max(ue - MF_START_COST, 0) - pc.tile0;
+    pc.units = ue - u;
     pc.n_ct_all = (ws.L + MF_TK - 1) / MF_TK;
     pc.kh = Kc + (long long)pc.head * p.sh;
     pc.vh = Vc + (long long)pc.head * p.sh;
     pc.pi = p.page_indices + ws.page0;
-    pc.item_a = Pt + (unsigned)(item * T);
+    pc.item_u = Pt + (unsigned)(item * Tu);
     return true;
+  };
+  unsigned g = g0;                                  // next unit of the share to hand out
+  auto next_piece = [&](Piece& pc) -> bool {       // the next piece that holds at least one tile
+    while (g < g1) {
+      if (!make_piece(g, pc)) return false;
+      g += (unsigned)pc.units;
+      if (pc.nt > 0) return true;
+    }
+    return false;
   };
 
   const unsigned lane_boff = (unsigned)(2 * ((long long)ld_key * p.st + ld_col));       // bytes within a cached 16-key slab
@@ -404,8 +428,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     const int T_row = pc.rt * ROWS_WG + ln.trow;
     ln.row_valid = T_row < rows_total;
     ln.wave_has_rows = pc.rt * ROWS_WG + ln.rb * 32 < rows_total;
-    ln.nn = T_row / p.G;
-    ln.hq = pc.head * p.G + T_row % p.G;
+    if (sc_.group_shift >= 0) {                   // heads per KV head a power of two: no division
+      ln.nn = T_row >> sc_.group_shift;
+      ln.hq = pc.head * p.G + (T_row & (p.G - 1));
+    } else {
+      ln.nn = T_row / p.G;
+      ln.hq = pc.head * p.G + T_row % p.G;
+    }
     return ln;
   };
 
@@ -425,21 +454,22 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   };
   auto start_loads = [&](const Piece& pc, const Lane& ln, const int (&id0)[MF_GROUPS], const int (&id1)[MF_GROUPS]) {
     const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(pc.s.row0 + (ln.row_valid ? ln.nn : 0)) * p.Hq + ln.hq) * MF_D + 8 * h;
+    if (ln.row_valid) {
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      u32x4 wq = {0u, 0u, 0u, 0u};
-      if (ln.row_valid) wq = *reinterpret_cast<const u32x4*>(qp + 16 * st);
-      qf[st] = as_bf16x8(wq);
+      for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * st));
+    } else {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(zero);
     }
     load_tile(pc, pc.tile0, id0, rA);
     if (pc.nt > 1 && DBG != 2) load_tile(pc, pc.tile0 + 1, id1, rB);
     fetch_pages(pc, pc.tile0 + 2, pg);
   };
 
-  unsigned g = g0;
   bool first_piece = true;
   Piece cur;
-  if (!make_piece(g, cur)) return;
+  if (!next_piece(cur)) return;
   Lane ln = make_lane(cur);
   int nid0[MF_GROUPS], nid1[MF_GROUPS];
 #pragma unroll
@@ -452,7 +482,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   while (have) {
     // descriptor and page ids of the piece after this one: in flight during the tile loop
     Piece nxt;
-    have = (g + (unsigned)cur.nt < g1) && make_piece(g + (unsigned)cur.nt, nxt);
+    have = next_piece(nxt);
     if (have) start_ids(nxt, nid0, nid1);
     const SeqInfo& s = cur.s;
     const int tile0 = cur.tile0, nt = cur.nt, n_ct_all = cur.n_ct_all, c1 = cur.s.L;
@@ -461,12 +491,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (tid == 0 && tile0 > 0 && tile0 + nt == cur.T) {
       // this item started in an earlier work-group and ends here: leave it to the combine kernel.
       // Its first piece sits in the work-group wf that owns the item's first tile, in slot 2 wf
-      // if the item begins exactly at wf's share, else 2 wf + 1; later pieces are in slots 2 w'.
-      const unsigned a = cur.item_a;
+      // if nothing of wf's share precedes the item, else 2 wf + 1; later pieces are in slots 2 w'.
+      const unsigned a = cur.item_u + MF_START_COST;       // the unit of the item's first tile
       int wf = min((int)(a / max(sh_q, 1u)), w);
       while (wf + 1 <= w && share_start(wf + 1) <= a) ++wf;
       while (wf > 0 && share_start(wf) > a) --wf;
-      const int first_slot = 2 * wf + (share_start(wf) == a ? 0 : 1);
+      // (a share that begins among the item's start-up units has nothing before the item's first tile)
+      const int first_slot = 2 * wf + (share_start(wf) >= cur.item_u ? 0 : 1);
       sc_.entries[w] = make_int4(cur.s.row0, cur.head | (cur.rt << 16), min(ROWS_WG, cur.s.n * p.G - cur.rt * ROWS_WG), first_slot);
     }
     const int RB = ln.RB, KQ = ln.KQ, rb = ln.rb, kq = ln.kq, trow = ln.trow, nn = ln.nn, hq = ln.hq;
@@ -598,27 +629,31 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
     FD_TLP(1);                                     // tiles done
     // ---- next piece: get its loads going before this one is merged and stored --------------
-    g += (unsigned)nt;
     Lane ln_next = ln;
     if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1); }
 
     FD_TLP(2);                                     // next piece requested
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
-    float* xch = reinterpret_cast<float*>(lds);                    // [wave][66][64] floats
+    f32x4* xch = reinterpret_cast<f32x4*>(lds);                    // [wave][17][64] quads: 16 of O, then (m, l)
     if (MAXRB != 4 && KQ > 1) {
       if (kq > 0 && kq < KQ) {
-        float* dst = xch + (size_t)wave * 66 * 64 + lane;
+        f32x4* dst = xch + (size_t)wave * 17 * 64 + lane;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) dst[(16 * b + i) * 64] = o[b][i];
-        dst[64 * 64] = m_run; dst[65 * 64] = l_lane;
+          for (int a = 0; a < 4; ++a) {
+            f32x4 q4 = {o[b][4 * a], o[b][4 * a + 1], o[b][4 * a + 2], o[b][4 * a + 3]};
+            dst[(4 * b + a) * 64] = q4;
+          }
+        f32x4 ml4 = {m_run, l_lane, 0.f, 0.f};
+        dst[16 * 64] = ml4;
       }
       __syncthreads();
       if (kq == 0) {
         for (int q2 = 1; q2 < KQ; ++q2) {
-          const float* src = xch + (size_t)(rb + q2 * RB) * 66 * 64 + lane;
-          const float m_o = src[64 * 64], l_o = src[65 * 64];
+          const f32x4* src = xch + (size_t)(rb + q2 * RB) * 17 * 64 + lane;
+          const f32x4 ml4 = src[16 * 64];
+          const float m_o = ml4[0], l_o = ml4[1];
           const float m_new = fmaxf(m_run, m_o);
           const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
           const float a = __builtin_amdgcn_exp2f(m_run - m_sub), bsc = __builtin_amdgcn_exp2f(m_o - m_sub);
@@ -627,7 +662,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
           for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a + src[(16 * b + i) * 64] * bsc;
+            for (int a4 = 0; a4 < 4; ++a4) {
+              const f32x4 q4 = src[(4 * b + a4) * 64];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[b][4 * a4 + e] = o[b][4 * a4 + e] * a + q4[e] * bsc;
+            }
         }
       }
     }
@@ -803,6 +842,8 @@ size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off
 static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaSched& sc, int& rows_wg) {
   sc.page_shift = 0;
   while ((1 << sc.page_shift) < p.page_size) ++sc.page_shift;
+  sc.group_shift = -1;
+  for (int b = 0; b < 16; ++b) if ((1 << b) == p.G) sc.group_shift = b;
   sc.num_wgs = attn_mfma_num_wgs();
   sc.min_share = 2;
   sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
