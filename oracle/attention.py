@@ -45,25 +45,36 @@ def to_f64(x: np.ndarray) -> np.ndarray:
     return np.asarray(x, dtype=np.float64)
 
 
-def visibility(L: int, k: int, m: int, v: int) -> np.ndarray:
+def visibility(L: int, k: int, m: int, v: int, nb: int = 1) -> np.ndarray:
     """Boolean [k+m, L+k+m]: may new row r look at key j?
 
     Keys 0..L-1 are the cached prefix, key L+t is new row t (verify rows first,
-    then the mask block).  Sec. 4.1: prefix visible to everyone; verify rows
-    causal among themselves and blind to mask tokens; mask rows see the first v
-    verify rows and their whole block.
+    then the mask rows).  Sec. 4.1: prefix visible to everyone; verify rows
+    causal among themselves and blind to mask tokens; a mask row sees the verify
+    rows its block is conditioned on and its whole block, both directions.
+
+    The m mask rows form nb blocks of m/nb rows each (Sec. 3, parallel
+    speculative decoding: one candidate block per hypothetical number of
+    accepted drafts; Sec. 4.1: blocks are isolated from one another).  Block b
+    is drafted under the hypothesis that the first v + b verify rows are the
+    clean context (never more than all k of them).
     """
+    if nb < 1 or m % nb:
+        raise ValueError("the mask rows must split evenly into the blocks")
     if not (0 <= v <= k):
         raise ValueError("mask_vis must lie in [0, verify_len]")
     n = k + m
+    mb = m // nb
     vis = np.zeros((n, L + n), dtype=bool)
     vis[:, :L] = True                       # cached clean prefix: every row sees it
     for r in range(n):
         for t in range(n):                  # new key t sits at column L + t
             if r < k:                       # verify row: causal, never a mask key
                 vis[r, L + t] = t <= r
-            else:                           # mask row
-                vis[r, L + t] = (t < v) or (t >= k)
+            else:                           # mask row of block b
+                b = (r - k) // mb
+                lo = k + b * mb
+                vis[r, L + t] = (t < min(v + b, k)) or (lo <= t < lo + mb)
     return vis
 
 
@@ -93,7 +104,7 @@ def masked_softmax_attention(q, keys, vals, vis, scale):
 
 
 def verify_draft_attention(q, k_new, v_new, k_cache, v_cache, page_indptr, page_indices,
-                           kv_len, row_indptr, verify_len, mask_vis=None, *,
+                           kv_len, row_indptr, verify_len, mask_vis=None, mask_blocks=None, *,
                            page_size: int, sm_scale: float | None = None,
                            return_probs: bool = False):
     """Hybrid-mask attention for a ragged batch.
@@ -104,7 +115,10 @@ def verify_draft_attention(q, k_new, v_new, k_cache, v_cache, page_indptr, page_
     k_cache, v_cache [P, Hkv, page_size, D]
     page_indices[page_indptr[i]:page_indptr[i+1]]  physical pages of sequence i
     kv_len[i]                 cached prefix tokens L_i (new rows excluded)
-    verify_len[i]             k_i;  m_i = rows_i - k_i;  mask_vis[i] = v_i (default k_i)
+    verify_len[i]             k_i;  m_i = rows_i - k_i
+    mask_blocks[i]            number of mask blocks nb_i (default 1)
+    mask_vis[i]               verify rows block 0 sees; block b sees b more
+                              (default k_i - nb_i + 1: the last block sees all)
 
     uint16 arrays are bf16 bit patterns.  Returns (out [R,Hq,D], lse [R,Hq]) in
     float64, plus the list of per-(sequence, head) probability matrices when
@@ -128,15 +142,16 @@ def verify_draft_attention(q, k_new, v_new, k_cache, v_cache, page_indptr, page_
         if n == 0:
             continue
         L = int(kv_len[i]); k = int(verify_len[i]); m = n - k
-        v = k if mask_vis is None else int(mask_vis[i])
         if m < 0:
             raise ValueError("verify_len exceeds the sequence's row count")
+        nb = 1 if mask_blocks is None else int(mask_blocks[i])
+        v = max(k - nb + 1, 0) if mask_vis is None else int(mask_vis[i])
         pages = np.asarray(page_indices[int(page_indptr[i]):int(page_indptr[i + 1])])
         Kc = gather_prefix(k_cache, pages, L, page_size)
         Vc = gather_prefix(v_cache, pages, L, page_size)
         keys = np.concatenate([Kc, k_new[r0:r1]], axis=0)      # [L+n, Hkv, D]
         vals = np.concatenate([Vc, v_new[r0:r1]], axis=0)
-        vis = visibility(L, k, m, v)
+        vis = visibility(L, k, m, v, nb)
         for h in range(Hq):
             g = h // G
             O, P, l = masked_softmax_attention(q[r0:r1, h], keys[:, g], vals[:, g], vis, scale)
@@ -147,3 +162,27 @@ def verify_draft_attention(q, k_new, v_new, k_cache, v_cache, page_indptr, page_
     if return_probs:
         return out, lse, probs
     return out, lse
+
+
+def select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis):
+    """Tokens of the candidate block that matches the verified outcome (Sec. 3,
+    parallel speculative decoding: once the number of accepted drafts r is known,
+    the branch drafted under that hypothesis is kept).
+
+    block_tokens[block_indptr[i]:block_indptr[i+1]] holds sequence i's nb_i blocks
+    of equal length back to back; block b was drafted with first_vis[i] + b verify
+    rows visible, i.e. (anchor row included) under the hypothesis of
+    first_vis[i] + b - 1 accepted drafts.  Returns a list of arrays, one per
+    sequence; the index is clamped to the blocks that exist.
+    """
+    out = []
+    for i in range(len(accept_len)):
+        toks = np.asarray(block_tokens[int(block_indptr[i]):int(block_indptr[i + 1])])
+        nb = int(mask_blocks[i])
+        if nb < 1 or len(toks) % nb:
+            raise ValueError("tokens must split evenly into the blocks")
+        mb = len(toks) // nb
+        b = int(accept_len[i]) + 1 - int(first_vis[i])
+        b = min(max(b, 0), nb - 1)
+        out.append(toks[b * mb:(b + 1) * mb].copy())
+    return out

@@ -269,3 +269,84 @@ def test_bf16_widening_is_exact():
     exp = torch.tensor(bits.astype(np.int16)).view(torch.bfloat16).double().numpy()
     assert np.array_equal(got, exp)
     assert got[0] == 1.0 and got[1] == -1.0 and got[2] == 3.140625 and np.isinf(got[5])
+
+
+# ---------------------------------------------------------------------------------------
+# Several mask blocks per sequence (Sec. 3, parallel speculative decoding; Sec. 4.1: blocks
+# are isolated from one another)
+# ---------------------------------------------------------------------------------------
+def _multi_block_case(seed, k=3, nb=3, mb=2, L=6):
+    c = _rand_case(seed, B=1, Ls=(L,), ks=(k,), ms=(nb * mb,))
+    return c, k, nb, mb
+
+
+def test_blocks_visible_sets_by_q_zero():
+    """Q = 0 makes every output the arithmetic mean of V over the visible set; the sets are
+    written out here row by row, independently of oracle.visibility."""
+    c, k, nb, mb = _multi_block_case(3)
+    c["q"][:] = 0.0
+    out, _ = _run(c, mask_blocks=[nb], mask_vis=[1])
+    Kc, Vc = _logical_kv(c, 0)
+    L = len(Vc)
+    for h in range(c["q"].shape[1]):
+        g = h // 2
+        vals = np.concatenate([Vc[:, g], c["v_new"][:, g]])
+        for r in range(k + nb * mb):
+            if r < k:
+                seen = list(range(L + r + 1))
+            else:
+                b = (r - k) // mb
+                seen = list(range(L)) + [L + t for t in range(1 + b)] + [L + k + b * mb + j for j in range(mb)]
+            np.testing.assert_allclose(out[r, h], vals[seen].mean(axis=0), atol=1e-12)
+
+
+def test_each_block_equals_a_single_block_call():
+    """Block b of a multi-block call == the (k, mb) single-block call fed that block's rows with
+    mask_vis = first_vis + b: reduces the new rule to the single-block rule pinned above."""
+    c, k, nb, mb = _multi_block_case(4, k=4, nb=3, mb=3, L=9)
+    out, lse = _run(c, mask_blocks=[nb], mask_vis=[2])
+    for b in range(nb):
+        rows = list(range(k)) + list(range(k + b * mb, k + (b + 1) * mb))
+        sub = dict(c)
+        for name in ("q", "k_new", "v_new"):
+            sub[name] = c[name][rows]
+        sub["row_indptr"] = np.array([0, len(rows)], dtype=np.int32)
+        o1, l1 = _run(sub, mask_vis=[min(2 + b, k)])
+        np.testing.assert_allclose(out[rows], o1, atol=1e-12)
+        np.testing.assert_allclose(lse[rows], l1, atol=1e-12)
+
+
+def test_blocks_are_isolated_and_invisible_to_verify_rows():
+    c, k, nb, mb = _multi_block_case(5, k=3, nb=3, mb=2)
+    base, _ = _run(c, mask_blocks=[nb])
+    pert = {n_: c[n_].copy() for n_ in ("q", "k_new", "v_new")}
+    blk1 = slice(k + mb, k + 2 * mb)
+    rng = np.random.default_rng(0)
+    for n_ in pert:
+        pert[n_][blk1] = rng.standard_normal(pert[n_][blk1].shape)
+    moved, _ = _run(dict(c, **pert), mask_blocks=[nb])
+    untouched = [r for r in range(k + nb * mb) if not (k + mb <= r < k + 2 * mb)]
+    assert np.array_equal(base[untouched], moved[untouched])
+    assert not np.array_equal(base[blk1], moved[blk1])
+
+
+def test_default_first_visibility_lets_the_last_block_see_every_verify_row():
+    c, k, nb, mb = _multi_block_case(6, k=3, nb=3, mb=2)
+    a, _ = _run(c, mask_blocks=[nb])
+    b, _ = _run(c, mask_blocks=[nb], mask_vis=[1])
+    assert np.array_equal(a, b)                      # k - nb + 1 = 1
+    one, _ = _run(c)                                  # one block of nb * mb rows sees all k rows
+    explicit, _ = _run(c, mask_blocks=[1], mask_vis=[k])
+    assert np.array_equal(one, explicit)
+    with pytest.raises(ValueError):
+        _run(c, mask_blocks=[4])                      # 6 mask rows do not split into 4 blocks
+
+
+def test_select_branch():
+    toks = np.arange(100, 100 + 12)                   # sequence 0: 3 blocks of 2; sequence 1: 2 blocks of 3
+    indptr = [0, 6, 12]
+    got = oa.select_branch(toks, indptr, [3, 2], accept_len=[1, 0], first_vis=[1, 2])
+    assert got[0].tolist() == [102, 103]              # r = 1 accepted -> block 1 (drafted seeing 2 rows)
+    assert got[1].tolist() == [106, 107, 108]         # r = 0 but the first block already assumes 1: clamped to block 0
+    got = oa.select_branch(toks, indptr, [3, 2], accept_len=[9, 2], first_vis=[1, 2])
+    assert got[0].tolist() == [104, 105] and got[1].tolist() == [109, 110, 111]
