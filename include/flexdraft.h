@@ -73,10 +73,14 @@ typedef enum fd_dtype { FD_F32 = 0, FD_BF16 = 1 } fd_dtype;
  * rows.  New row r may look at
  *     every cached token;
  *     if r < k_i  (verify row): new rows t <= r        (causal; never a mask token)
- *     if r >= k_i (mask row):   new rows t < v_i, and every mask row t >= k_i
- *                               (its own block, both directions)
- * where v_i = mask_vis[i] (default k_i) is the number of verify rows the block is
- * conditioned on (the accepted-count hypothesis of Eq. 2).  The output row is
+ *     if r >= k_i (mask row of block b): new rows t < v_ib, and the rows of its own
+ *                               block (both directions); never another block
+ * The n_i - k_i mask rows form nb_i = mask_blocks[i] (default 1) blocks of equal
+ * length, one candidate draft per hypothetical number of accepted drafts (Sec. 3,
+ * parallel speculative decoding; Sec. 4.1: blocks are isolated from one another).
+ * Block b is conditioned on the first v_ib = min(v_i + b, k_i) verify rows, with
+ * v_i = mask_vis[i] (default k_i - nb_i + 1, so that the last block sees every
+ * verify row; with one block: all of them).  The output row is
  *     out[r,h] = sum_j softmax_j(sm_scale * q[r,h].k[j,h/G]) v[j,h/G]   over visible j,
  * G = num_q_heads / num_kv_heads; lse[r,h] (optional) is the natural-log
  * normaliser  log sum_j exp(sm_scale * q.k_j).
@@ -120,7 +124,8 @@ typedef struct fd_attn_args {
   const int32_t *kv_len;      /* device [B]                                                   */
   const int32_t *row_indptr;  /* device [B+1]                                                 */
   const int32_t *verify_len;  /* device [B]   k_i in [0, n_i]                                 */
-  const int32_t *mask_vis;    /* device [B] or NULL (=> v_i = k_i); 0 <= v_i <= k_i           */
+  const int32_t *mask_vis;    /* device [B] or NULL (=> v_i = k_i - nb_i + 1); 0 <= v_i <= k_i */
+  const int32_t *mask_blocks; /* device [B] or NULL (=> nb_i = 1); nb_i >= 1 divides n_i - k_i */
   const void *q;              /* device                                                       */
   const void *k_new;          /* device                                                       */
   const void *v_new;          /* device                                                       */

@@ -133,7 +133,7 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
 extern "C" {
 
 const char* fd_last_error(void) { return g_err; }
-const char* fd_version(void) { return "flexdraft-gfx950 0.1"; }
+const char* fd_version(void) { return "flexdraft-gfx950 0.2"; }
 
 size_t fd_verify_draft_attn_workspace(const fd_attn_args* a) {
   AttnPlan plan;
@@ -177,6 +177,7 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
   p.page_indptr = a->page_indptr; p.page_indices = a->page_indices; p.kv_len = a->kv_len;
   p.row_indptr = a->row_indptr; p.verify_len = a->verify_len; p.mask_vis = a->mask_vis;
+  p.mask_blocks = a->mask_blocks;
   p.q = a->q; p.k_new = a->k_new; p.v_new = a->v_new; p.out = a->out; p.lse = a->lse;
   p.part_acc = reinterpret_cast<float*>(a->workspace);
   p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a->workspace) + plan.acc_bytes);

@@ -56,6 +56,7 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
   const int sub = tid % 16;
   const int my_T = rt * GEN_ROWS + my_row;
   const int my_nn = my_T / p.G;           // new-row index of my tile row
+  const RowWindow my_win = row_window(my_nn < s.n ? my_nn : 0, s);
   float m_run = -INFINITY, l_run = 0.f;
   float acc[GEN_DMAX / 16];
 #pragma unroll
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
       float dot = 0.f;
       for (int d = 0; d < D; ++d) dot = fmaf(Qs[my_row][d], Ks[kk][d], dot);
       int key = base + kk;
-      bool vis = is_new ? new_key_visible(my_nn, key, s.n, s.k, s.v) : (key < c1);
+      bool vis = is_new ? (new_key_visible(my_win, key) && key < s.n) : (key < c1);
       Ps[my_row][kk] = vis ? dot * p.sm_scale : -INFINITY;
     }
     __syncthreads();

@@ -82,14 +82,6 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
-// Branch-free form of the Sec. 4.1 rule for new row r looking at new row t.
-__device__ __forceinline__ bool new_vis(int r, int t, int n, int k, int v) {
-  const bool verify_row = r < k;
-  const bool a = t <= r;
-  const bool b = (t < v) | (t >= k);
-  return (t < n) & (verify_row ? a : b);
-}
-
 // Tiles of one item of this sequence, and how many items (heads x row blocks) it has.
 __device__ __forceinline__ void seq_shape(const AttnParams& p, const SeqInfo& s, int rows_wg, int& tiles, int& items) {
   if (s.n <= 0) { tiles = 0; items = 0; return; }
@@ -193,7 +185,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (lo <= g0 && g0 < hi) {
       sh_found[0] = tid; sh_found[1] = (int)lo;
       sh_found[2] = s_mine.L; sh_found[3] = s_mine.row0; sh_found[4] = s_mine.n; sh_found[5] = s_mine.k;
-      sh_found[6] = s_mine.v; sh_found[7] = s_mine.page0; sh_found[8] = s_mine.npages;
+      sh_found[6] = s_mine.v; sh_found[7] = s_mine.page0; sh_found[8] = s_mine.npages; sh_found[9] = s_mine.nb;
     }
     if (bad) flag_status(p.status, bad);
     __syncthreads();
@@ -204,7 +196,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     ws.L = __builtin_amdgcn_readfirstlane(sh_found[2]);      ws.row0 = __builtin_amdgcn_readfirstlane(sh_found[3]);
     ws.n = __builtin_amdgcn_readfirstlane(sh_found[4]);      ws.k = __builtin_amdgcn_readfirstlane(sh_found[5]);
     ws.v = __builtin_amdgcn_readfirstlane(sh_found[6]);      ws.page0 = __builtin_amdgcn_readfirstlane(sh_found[7]);
-    ws.npages = __builtin_amdgcn_readfirstlane(sh_found[8]);
+    ws.npages = __builtin_amdgcn_readfirstlane(sh_found[8]); ws.nb = __builtin_amdgcn_readfirstlane(sh_found[9]);
   } else {
     // larger batches: a first pass for the total, a second, block by block, for the owner of g0
     int part = 0;
@@ -262,7 +254,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     s.L = __builtin_amdgcn_readfirstlane(s.L);       s.row0 = __builtin_amdgcn_readfirstlane(s.row0);
     s.n = __builtin_amdgcn_readfirstlane(s.n);       s.k = __builtin_amdgcn_readfirstlane(s.k);
     s.v = __builtin_amdgcn_readfirstlane(s.v);       s.page0 = __builtin_amdgcn_readfirstlane(s.page0);
-    s.npages = __builtin_amdgcn_readfirstlane(s.npages);
+    s.npages = __builtin_amdgcn_readfirstlane(s.npages); s.nb = __builtin_amdgcn_readfirstlane(s.nb);
     return s;
   };
   // ---- walk over the share, one piece (run of tiles inside one item) at a time ----------------
@@ -413,6 +405,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // Per-lane view of a piece: which query row this lane owns and the wave's role.
   struct Lane {
     int RB, KQ, rb, kq, trow, nn, hq;
+    RowWindow win;              // what this lane's row sees among the new rows
     bool row_valid, wave_has_rows;
   };
   auto make_lane = [&](const Piece& pc) {
@@ -435,6 +428,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       ln.nn = T_row / p.G;
       ln.hq = pc.head * p.G + T_row % p.G;
     }
+    ln.win = row_window(ln.row_valid ? ln.nn : 0, pc.s);
     return ln;
   };
 
@@ -556,7 +550,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               int key = tile_base + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-              bool vis = is_new ? new_vis(nn, key, s.n, s.k, s.v) : (key < c1);
+              bool vis = is_new ? new_key_visible(ln.win, key) : (key < c1);
               sc[i] = vis ? sc[i] : -INFINITY;
             }
           }

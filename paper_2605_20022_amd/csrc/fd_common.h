@@ -56,7 +56,8 @@ struct SeqInfo {
   int row0;     // first packed row
   int n;        // new rows
   int k;        // verify rows
-  int v;        // verify rows visible to the mask block
+  int v;        // verify rows visible to mask block 0 (block b sees b more, at most k)
+  int nb;       // mask blocks (n - k splits evenly into them)
   int page0;    // first entry in page_indices
   int npages;   // entries available
 };
@@ -71,7 +72,7 @@ struct AttnParams {
   const void* k_cache; const void* v_cache;
   long long sp, sh, st;                       // cache strides in elements
   const int* page_indptr; const int* page_indices; const int* kv_len;
-  const int* row_indptr; const int* verify_len; const int* mask_vis;
+  const int* row_indptr; const int* verify_len; const int* mask_vis; const int* mask_blocks;
   const void* q; const void* k_new; const void* v_new;
   void* out; float* lse;
   float* part_acc;    // [max_chunks][R][Hq][D]
@@ -103,7 +104,13 @@ __device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i, uint32
   if (s.row0 + s.n > p.total_rows) s.n = p.total_rows - s.row0;
   if (k < 0 || k > s.n) bad |= FD_DEV_ROWS_RANGE;
   s.k = clampi(k, 0, s.n);
-  int v = s.k;
+  int nb = 1;
+  if (p.mask_blocks) {
+    nb = ld(p.mask_blocks, i);
+    if (nb < 1 || (s.n - s.k) % (nb < 1 ? 1 : nb)) { bad |= FD_DEV_ROWS_RANGE; nb = 1; }
+  }
+  s.nb = nb;
+  int v = s.k - nb + 1 < 0 ? 0 : s.k - nb + 1;
   if (p.mask_vis) {
     v = ld(p.mask_vis, i);
     if (v < 0 || v > s.k) bad |= FD_DEV_ROWS_RANGE;
@@ -124,10 +131,22 @@ __device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i, uint32
 
 __device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) { return load_seq_t<true>(p, i); }
 
-// May new row `r` (0-based within the sequence) look at new row `t`?  Sec. 4.1 mask rules.
-__device__ __forceinline__ bool new_key_visible(int r, int t, int n, int k, int v) {
-  if (t >= n) return false;
-  return r < k ? (t <= r) : (t < v || t >= k);
+// What new row r (0-based within the sequence) sees among the new rows, Sec. 4.1: the rows
+// t < vr, and the rows lo <= t < hi.  A verify row is causal (vr = r + 1, no second range); a
+// mask row of block b sees the first min(v + b, k) verify rows and its own block.
+struct RowWindow { int vr, lo, hi; };
+__device__ __forceinline__ RowWindow row_window(int r, const SeqInfo& s) {
+  RowWindow w;
+  if (r < s.k) { w.vr = r + 1; w.lo = 0; w.hi = 0; return w; }
+  const int mb = (s.n - s.k) / s.nb;                // >= 1 whenever a mask row exists
+  const int b = (r - s.k) / (mb > 0 ? mb : 1);
+  w.vr = s.v + b < s.k ? s.v + b : s.k;
+  w.lo = s.k + b * mb;
+  w.hi = w.lo + mb;
+  return w;
+}
+__device__ __forceinline__ bool new_key_visible(const RowWindow& w, int t) {
+  return (t < w.vr) | ((t >= w.lo) & (t < w.hi));
 }
 
 }  // namespace fd

@@ -33,6 +33,7 @@ class fd_attn_args(C.Structure):
         ("cache_stride_page", C.c_int64), ("cache_stride_head", C.c_int64), ("cache_stride_token", C.c_int64),
         ("page_indptr", C.c_void_p), ("page_indices", C.c_void_p), ("kv_len", C.c_void_p),
         ("row_indptr", C.c_void_p), ("verify_len", C.c_void_p), ("mask_vis", C.c_void_p),
+        ("mask_blocks", C.c_void_p),
         ("q", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p),
         ("out", C.c_void_p), ("lse", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
@@ -119,7 +120,7 @@ def _i32(t: torch.Tensor, name: str) -> torch.Tensor:
 
 
 def make_attn_args(q, k_new, v_new, k_cache, v_cache, page_indptr, page_indices, kv_len, row_indptr,
-                   verify_len, mask_vis=None, *, out, lse=None, max_kv_len: int, max_new_rows: int,
+                   verify_len, mask_vis=None, mask_blocks=None, *, out, lse=None, max_kv_len: int, max_new_rows: int,
                    sm_scale: float = 0.0, flags: int = 0, kv_chunk: int = 0, workspace=None, status=None):
     """Fill an fd_attn_args from tensors.  k_cache / v_cache: [pages, Hkv, page_size, D] views
     (any strides with a contiguous last dimension)."""
@@ -144,6 +145,7 @@ def make_attn_args(q, k_new, v_new, k_cache, v_cache, page_indptr, page_indices,
     a.row_indptr = _i32(row_indptr, "row_indptr").data_ptr()
     a.verify_len = _i32(verify_len, "verify_len").data_ptr()
     a.mask_vis = None if mask_vis is None else _i32(mask_vis, "mask_vis").data_ptr()
+    a.mask_blocks = None if mask_blocks is None else _i32(mask_blocks, "mask_blocks").data_ptr()
     a.q = q.data_ptr(); a.k_new = k_new.data_ptr(); a.v_new = v_new.data_ptr()
     a.out = out.data_ptr(); a.lse = None if lse is None else lse.data_ptr()
     if workspace is not None:

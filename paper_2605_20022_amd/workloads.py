@@ -66,11 +66,12 @@ class AttnWorkload:
     page_size: int
     kv_len_range: tuple             # inclusive (lo, hi); lo == hi for fixed length
     verify_len_range: tuple         # inclusive (lo, hi) for k_i
-    mask_len: int                   # m (same for every sequence)
+    mask_len: int                   # m: length of one mask block (same for every sequence)
     std: float                      # standard deviation of Q, K, V entries
     shuffled_pages: bool = True
     spare_page_frac: float = 0.03   # unused physical pages left in the pool
     seed: int = BASE_SEED
+    mask_blocks: int = 1            # 0: one block per verify row (full parallel mode), else that many blocks
 
     def scaled(self, **kw) -> "AttnWorkload":
         d = dict(self.__dict__); d.update(kw)
@@ -115,6 +116,11 @@ CONFIGS = {
                           seed=BASE_SEED + 4),
              AcceptWorkload("cfg5", "bf16", VOCAB_QWEN3, "sample", 2.0, draft_noise_std=0.5,
                             temperature=1.0, seed=BASE_SEED + 4)),
+    # beyond the five benchmark configurations: full parallel mode, one candidate block of 8 mask
+    # tokens per hypothetical number of accepted drafts (4 verify rows -> 4 blocks, 36 new rows)
+    "par4": (AttnWorkload("par4", "bf16", 8, 32, 8, 128, 16, (2048, 8192), (4, 4), 8, _INV_SQRT_128,
+                          seed=BASE_SEED + 5, mask_blocks=0),
+             None),
 }
 
 
@@ -126,7 +132,8 @@ def make_lengths(w: AttnWorkload):
     kv_len = rng.integers(lo, hi + 1, size=B, dtype=np.int64).astype(np.int32)
     klo, khi = w.verify_len_range
     verify_len = rng.integers(klo, khi + 1, size=B, dtype=np.int64).astype(np.int32)
-    rows = verify_len + np.int32(w.mask_len)
+    blocks = verify_len.copy() if w.mask_blocks == 0 else np.full(B, w.mask_blocks, dtype=np.int32)
+    rows = verify_len + blocks * np.int32(w.mask_len)
     row_indptr = np.zeros(B + 1, dtype=np.int32)
     row_indptr[1:] = np.cumsum(rows)
     pages_per_seq = (kv_len.astype(np.int64) + ps - 1) // ps
@@ -139,7 +146,8 @@ def make_lengths(w: AttnWorkload):
     else:
         page_indices = np.arange(used, dtype=np.int32)
     return dict(kv_len=kv_len, verify_len=verify_len, row_indptr=row_indptr,
-                page_indptr=page_indptr, page_indices=page_indices, num_pages=num_pages)
+                page_indptr=page_indptr, page_indices=page_indices, num_pages=num_pages,
+                mask_blocks=(None if w.mask_blocks == 1 else blocks.astype(np.int32)))
 
 
 def make_attention_inputs(w: AttnWorkload, *, std: Optional[float] = None):

@@ -38,6 +38,8 @@ class AttnCall:
         if d["page_indices"].numel() == 0:
             d["page_indices"] = torch.zeros(1, dtype=torch.int32, device="cuda")
         d["mask_vis"] = None if mask_vis is None else torch.from_numpy(np.asarray(mask_vis, dtype=np.int32)).cuda()
+        mb = inp.get("mask_blocks")
+        d["mask_blocks"] = None if mb is None else torch.from_numpy(np.asarray(mb, dtype=np.int32)).cuda()
         self.d = d
         R, Hq, D = d["q"].shape
         self.out = torch.full((R, Hq, D), float("nan"), dtype=d["q"].dtype, device="cuda")
@@ -48,7 +50,7 @@ class AttnCall:
         self.max_new_rows = int(rows.max()) if max_new_rows is None and len(rows) else (max_new_rows or 0)
         self.args = fd.make_attn_args(
             d["q"], d["k_new"], d["v_new"], d["k_cache"], d["v_cache"], d["page_indptr"], d["page_indices"],
-            d["kv_len"], d["row_indptr"], d["verify_len"], d["mask_vis"], out=self.out, lse=self.lse,
+            d["kv_len"], d["row_indptr"], d["verify_len"], d["mask_vis"], d["mask_blocks"], out=self.out, lse=self.lse,
             max_kv_len=self.max_kv_len, max_new_rows=self.max_new_rows, sm_scale=sm_scale, flags=flags,
             kv_chunk=kv_chunk, status=self.status)
         need = fd.fd_verify_draft_attn_workspace(self.args)
@@ -73,6 +75,8 @@ def subset_inputs(inp: dict, ids) -> dict:
         sub[k] = inp[k][keep]
     sub["kv_len"] = inp["kv_len"][ids]
     sub["verify_len"] = inp["verify_len"][ids]
+    if inp.get("mask_blocks") is not None:
+        sub["mask_blocks"] = np.asarray(inp["mask_blocks"])[ids]
     sub["row_indptr"] = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
     pages = [inp["page_indices"][inp["page_indptr"][i]:inp["page_indptr"][i + 1]] for i in ids]
     sub["page_indices"] = np.concatenate(pages).astype(np.int32) if pages else np.zeros(0, dtype=np.int32)
@@ -86,7 +90,7 @@ def oracle_attention(inp: dict, mask_vis=None, sm_scale=None):
     return oa.verify_draft_attention(
         inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"], inp["v_cache"], inp["page_indptr"],
         inp["page_indices"], inp["kv_len"], inp["row_indptr"], inp["verify_len"], mask_vis,
-        page_size=ps, sm_scale=sm_scale)
+        inp.get("mask_blocks"), page_size=ps, sm_scale=sm_scale)
 
 
 def assert_attn_close(got, ref, dtype: str, what=""):

@@ -83,6 +83,54 @@ def test_mfma_kernel_small_cases(fd, case):
     assert np.abs(a - b).max() <= 2e-2
 
 
+@pytest.mark.parametrize("case", [
+    # (k verify rows, blocks, block length): full parallel mode has one block per verify row
+    dict(B=3, G=4, Hkv=2, D=128, ps=16, kv=(100, 600), k=4, nb=4, mb=3, dtype="bf16"),
+    dict(B=2, G=4, Hkv=1, D=128, ps=16, kv=(300, 900), k=6, nb=3, mb=8, dtype="bf16"),      # pruned hypotheses, 30 rows
+    dict(B=2, G=2, Hkv=2, D=64, ps=8, kv=(20, 90), k=3, nb=3, mb=2, dtype="f32"),           # scalar fp32 kernel
+])
+def test_several_mask_blocks(fd, case):
+    """One candidate block per hypothetical number of accepted drafts (Sec. 3, parallel
+    speculative decoding): block b sees the first first_vis + b verify rows and itself only."""
+    w = W.AttnWorkload("blocks", case["dtype"], case["B"], case["G"] * case["Hkv"], case["Hkv"], case["D"],
+                       case["ps"], case["kv"], (case["k"], case["k"]), case["mb"], 1.0, seed=71,
+                       mask_blocks=case["nb"])
+    inp = W.make_attention_inputs(w)
+    assert inp["mask_blocks"] is not None and int(np.diff(inp["row_indptr"])[0]) == case["k"] + case["nb"] * case["mb"]
+    _check(fd, inp, case["dtype"], f"blocks {case} default visibility")
+    _check(fd, inp, case["dtype"], f"blocks {case} first_vis=1", mask_vis=[1] * case["B"])
+    if case["dtype"] == "bf16":
+        _check(fd, inp, "bf16", f"blocks {case} generic", flags=FORCE_GENERIC)
+    # perturbing one block moves that block only (checked on the device result itself)
+    base, _ = AttnCall(fd, inp).run()
+    pert = dict(inp)
+    k, mb = case["k"], case["mb"]
+    blk = np.zeros(inp["q"].shape[0], dtype=bool)
+    for i in range(case["B"]):
+        r0 = int(inp["row_indptr"][i])
+        blk[r0 + k + mb: r0 + k + 2 * mb] = True              # block 1 of every sequence
+    rng = np.random.default_rng(1)
+    for name in ("q", "k_new", "v_new"):
+        x = inp[name].copy()
+        noise = rng.standard_normal(x[blk].shape).astype(np.float32) * 2
+        x[blk] = W.f32_to_bf16_bits(noise) if case["dtype"] == "bf16" else noise
+        pert[name] = x
+    moved, _ = AttnCall(fd, pert).run()
+    assert np.array_equal(base[~blk], moved[~blk])
+    assert not np.array_equal(base[blk], moved[blk])
+
+
+def test_par4_full_parallel_mode(fd):
+    w, _ = W.CONFIGS["par4"]
+    inp = W.make_attention_inputs(w)
+    out, lse = AttnCall(fd, inp).run()
+    assert np.isfinite(out).all()
+    sub = subset_inputs(inp, [0, 5])
+    ref, ref_lse = oracle_attention(sub)
+    assert_attn_close(out[sub["_rows"]], ref, "bf16", "par4 sample")
+    assert np.abs(lse[sub["_rows"]] - ref_lse).max() <= 2e-2
+
+
 def test_mfma_strided_cache_layout(fd):
     """Token-major cache ([page][slot][head][D]) addressed through the stride arguments."""
     w = _wl("nhd", "bf16", 3, 8, 2, 128, 16, (10, 400), (2, 6), 6, seed=31)
