@@ -190,6 +190,28 @@ FD_API fd_status fd_accept_sample(const void *target_logits, const void *draft_l
 /* Workspace bytes for the acceptance calls (sampling != 0 for fd_accept_sample); 0 on invalid arguments. */
 FD_API size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling);
 
+/*
+ * Branch selection of parallel speculative decoding (Sec. 3): the forward pass prepared one
+ * candidate block per hypothetical number of accepted drafts; once acceptance has fixed that
+ * number, the block drafted under it becomes the next draft.
+ *   block_tokens  device int32 [total_tokens]: the drafted tokens of every block; sequence i
+ *                 owns block_indptr[i] .. block_indptr[i+1], its nb_i = mask_blocks[i] blocks
+ *                 of equal length back to back
+ *   first_vis     device int32 [B] or NULL (=> 1): verify rows block 0 was conditioned on
+ *                 (fd_attn_args.mask_vis); block b assumed first_vis[i] + b - 1 accepted drafts
+ *   accept_len    device int32 [B]: accepted drafts r_i (fd_accept_greedy / fd_accept_sample)
+ *   out_tokens    device int32 [B][out_stride]: the chosen block, padded with -1
+ *   out_block     device int32 [B] or NULL: index of the chosen block
+ * The block index r_i + 1 - first_vis[i] is clamped to the blocks that exist.  A sequence
+ * whose tokens do not split into nb_i >= 1 blocks, or whose block is longer than out_stride,
+ * gets -1 everywhere.  Asynchronous on hip_stream.  Errors: FD_ERR_INVALID_ARG, FD_ERR_HIP.
+ */
+FD_API fd_status fd_select_branch(const int32_t *block_tokens, const int32_t *block_indptr,
+                                  const int32_t *mask_blocks, const int32_t *accept_len,
+                                  const int32_t *first_vis, int32_t batch, int32_t total_tokens,
+                                  int32_t out_stride, int32_t *out_tokens, int32_t *out_block,
+                                  void *hip_stream);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 FD_API const char *fd_last_error(void);
 

@@ -11,6 +11,9 @@ namespace fd {
 hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
 hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int skip_single, hipStream_t st);
 bool attn_mfma_supports(int dtype, int head_dim, int page_size);
+hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, const int* mask_blocks,
+                             const int* accept_len, const int* first_vis, int batch, int total_tokens,
+                             int out_stride, int* out_tokens, int* out_block, hipStream_t st);
 int attn_mfma_tile_keys();
 int attn_mfma_rows_per_wg(int max_tile_rows);
 hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, hipStream_t st);
@@ -297,6 +300,21 @@ int32_t fd_profile_end(float* ms_out, int32_t capacity) {
   for (int i = 0; i < 2 * g_prof_cap; ++i) (void)hipEventDestroy(g_prof_events[i]);
   delete[] g_prof_events; g_prof_events = nullptr; g_prof_cap = g_prof_used = 0;
   return n;
+}
+
+fd_status fd_select_branch(const int32_t* block_tokens, const int32_t* block_indptr, const int32_t* mask_blocks,
+                           const int32_t* accept_len, const int32_t* first_vis, int32_t batch, int32_t total_tokens,
+                           int32_t out_stride, int32_t* out_tokens, int32_t* out_block, void* hip_stream) {
+  if (batch < 0 || total_tokens < 0 || out_stride < 0) return fail(FD_ERR_INVALID_ARG, "negative size");
+  g_err[0] = 0;
+  if (batch == 0) return FD_OK;
+  if (!block_indptr || !mask_blocks || !accept_len || (!out_tokens && out_stride > 0) || (!block_tokens && total_tokens > 0))
+    return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
+  hipError_t e = fd::run_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis, batch,
+                                       total_tokens, out_stride, out_tokens, out_block,
+                                       reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "select_branch launch: %s", hipGetErrorString(e));
+  return FD_OK;
 }
 
 fd_status fd_stream_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {

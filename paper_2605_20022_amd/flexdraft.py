@@ -50,7 +50,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
+           "fd_accept_workspace", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
            "fd_version"]
 
 
@@ -78,6 +78,8 @@ def load() -> C.CDLL:
                                      C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fd_accept_workspace.restype = C.c_size_t
     lib.fd_accept_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.fd_select_branch.restype = C.c_int
+    lib.fd_select_branch.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3
     lib.fd_last_error.restype = C.c_char_p
     lib.fd_profile_begin.restype = C.c_int
     lib.fd_profile_begin.argtypes = [C.c_int32]
@@ -209,6 +211,17 @@ def fd_profile_end(capacity: int):
     buf = (C.c_float * capacity)()
     n = load().fd_profile_end(buf, capacity)
     return [buf[i] for i in range(n)]
+
+
+def fd_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, out_tokens, *, first_vis=None,
+                     out_block=None, stream=None) -> None:
+    B = accept_len.shape[0]
+    _check(load().fd_select_branch(
+        _ptr(_i32(block_tokens, "block_tokens")), _ptr(_i32(block_indptr, "block_indptr")),
+        _ptr(_i32(mask_blocks, "mask_blocks")), _ptr(_i32(accept_len, "accept_len")),
+        None if first_vis is None else _ptr(_i32(first_vis, "first_vis")), B, block_tokens.numel(),
+        out_tokens.shape[1], _ptr(_i32(out_tokens, "out_tokens")),
+        None if out_block is None else _ptr(_i32(out_block, "out_block")), _stream(stream)))
 
 
 def fd_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

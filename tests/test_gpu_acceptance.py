@@ -7,6 +7,7 @@ thin-margin decision may land on the adjacent outcome, which is verified to be a
 """
 import numpy as np
 import pytest
+import torch
 
 from oracle import acceptance as oc
 from paper_2605_20022_amd import workloads as W
@@ -151,3 +152,41 @@ def test_acceptance_argument_errors(fd):
     with pytest.raises(fd.FlexDraftError) as e:
         fd.fd_accept_sample(lg, lg, ip, tk, u, u, acc, bon, temperature=0.0, max_rows_per_seq=2, workspace=ws)
     assert e.value.code == 1
+
+
+def test_select_branch_matches_oracle(fd):
+    """fd_select_branch against oracle.attention.select_branch on a ragged batch, including
+    indices that need clamping and a sequence whose tokens do not split into its blocks."""
+    from oracle import attention as oa
+    rng = np.random.default_rng(9)
+    B = 37
+    nb = rng.integers(1, 6, size=B).astype(np.int32)
+    mb = rng.integers(1, 17, size=B).astype(np.int32)
+    lens = nb * mb
+    lens[5] += 1 if nb[5] > 1 else 0                          # does not split evenly (when nb > 1)
+    indptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    toks = rng.integers(0, 151936, size=int(indptr[-1])).astype(np.int32)
+    acc = rng.integers(0, 8, size=B).astype(np.int32)
+    fv = rng.integers(0, 4, size=B).astype(np.int32)
+    stride = 16
+    out = torch.full((B, stride), -7, dtype=torch.int32, device="cuda")
+    blk = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    dev = lambda a: torch.from_numpy(a).cuda()
+    fd.fd_select_branch(dev(toks), dev(indptr), dev(nb), dev(acc), out, first_vis=dev(fv), out_block=blk)
+    torch.cuda.synchronize()
+    got, gb = out.cpu().numpy(), blk.cpu().numpy()
+    for i in range(B):
+        if lens[i] % nb[i]:
+            assert (got[i] == -1).all() and gb[i] == -1
+            continue
+        ref = oa.select_branch(toks[indptr[i]:indptr[i + 1]], [0, lens[i]], [nb[i]], [acc[i]], [fv[i]])
+        m = lens[i] // nb[i]
+        assert got[i, :m].tolist() == ref[0].tolist() and (got[i, m:] == -1).all()
+        assert gb[i] == min(max(acc[i] + 1 - fv[i], 0), nb[i] - 1)
+    # default first_vis = 1: block index = accepted drafts
+    fd.fd_select_branch(dev(toks), dev(indptr), dev(nb), dev(acc), out, out_block=blk)
+    torch.cuda.synchronize()
+    gb = blk.cpu().numpy()
+    for i in range(B):
+        if lens[i] % nb[i] == 0:
+            assert gb[i] == min(acc[i], nb[i] - 1)
