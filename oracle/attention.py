@@ -186,3 +186,35 @@ def select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis
         b = min(max(b, 0), nb - 1)
         out.append(toks[b * mb:(b + 1) * mb].copy())
     return out
+
+
+def append_accepted_kv(k_cache, v_cache, k_new, v_new, page_indptr, page_indices, kv_len, row_indptr,
+                       accept_len, *, page_size: int):
+    """Make the verified rows part of the clean prefix (Sec. 4.3, decoupled execution: the KV cache
+    written by target verification is what the next draft step reuses).
+
+    Sequence i commits its anchor row and its first accept_len[i] drafts, i.e. new rows
+    0 .. accept_len[i] (the bonus token has no K/V yet: it is the next step's anchor).  Row j goes
+    to logical position kv_len[i] + j: page page_indices[page_indptr[i] + pos // page_size], slot
+    pos % page_size.  Works on copies; returns (k_cache, v_cache, new kv_len).  Arrays keep their
+    dtype (bf16 bit patterns are moved as they are).
+    """
+    kc, vc = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    new_len = np.array(kv_len, dtype=np.int32, copy=True)
+    for i in range(len(kv_len)):
+        r0, n = int(row_indptr[i]), int(row_indptr[i + 1]) - int(row_indptr[i])
+        if n == 0:
+            continue
+        take = int(accept_len[i]) + 1
+        if take > n:
+            raise ValueError("more rows committed than the sequence has")
+        pages = np.asarray(page_indices[int(page_indptr[i]):int(page_indptr[i + 1])])
+        for j in range(take):
+            pos = int(kv_len[i]) + j
+            if pos // page_size >= len(pages):
+                raise ValueError("the page list has no room for the committed rows")
+            pg = int(pages[pos // page_size])
+            kc[pg, :, pos % page_size, :] = k_new[r0 + j]
+            vc[pg, :, pos % page_size, :] = v_new[r0 + j]
+        new_len[i] += take
+    return kc, vc, new_len

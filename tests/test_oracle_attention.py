@@ -350,3 +350,45 @@ def test_select_branch():
     assert got[1].tolist() == [106, 107, 108]         # r = 0 but the first block already assumes 1: clamped to block 0
     got = oa.select_branch(toks, indptr, [3, 2], accept_len=[9, 2], first_vis=[1, 2])
     assert got[0].tolist() == [104, 105] and got[1].tolist() == [109, 110, 111]
+
+
+def test_append_accepted_kv_then_attend_equals_attending_with_the_rows_as_new_rows():
+    """After committing the anchor and r accepted drafts, a plain decode query over the longer prefix
+    must see exactly what a verify row r of the original call saw: prefix + new rows 0..r (causal).
+    Independent of the append code: the expected value comes from the un-appended call."""
+    ps = 4
+    c = _rand_case(11, B=2, Ls=(5, 10), ks=(4, 3), ms=(2, 0), ps=ps)
+    # give every sequence spare pages for the rows that may be committed
+    pages = []
+    extra = 2
+    P0 = c["k_cache"].shape[0]
+    rng = np.random.default_rng(2)
+    grow = rng.standard_normal((2 * extra,) + c["k_cache"].shape[1:])
+    c["k_cache"] = np.concatenate([c["k_cache"], grow]); c["v_cache"] = np.concatenate([c["v_cache"], grow * 0.5])
+    new_indptr = [0]
+    for i in range(2):
+        own = list(c["page_indices"][c["page_indptr"][i]:c["page_indptr"][i + 1]]) + [P0 + i * extra + e for e in range(extra)]
+        pages += own; new_indptr.append(len(pages))
+    c["page_indices"] = np.array(pages, dtype=np.int32); c["page_indptr"] = np.array(new_indptr, dtype=np.int32)
+    base, _ = _run(c)
+    acc = [2, 0]
+    kc, vc, new_len = oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"],
+                                            c["page_indices"], c["kv_len"], c["row_indptr"], acc, page_size=ps)
+    assert new_len.tolist() == [5 + 3, 10 + 1]
+    # untouched slots keep their values
+    assert (kc != c["k_cache"]).any(axis=(1, 3)).sum() == 4          # 3 + 1 (page, slot) pairs rewritten
+    for i in range(2):
+        r = acc[i]                                                    # last committed row
+        row = int(c["row_indptr"][i]) + r
+        # the last committed row queried again as the only new row over the prefix before it
+        d = dict(c, k_cache=kc, v_cache=vc,
+                 kv_len=np.array([new_len[i] - 1], dtype=np.int32),
+                 page_indptr=np.array([0, c["page_indptr"][i + 1] - c["page_indptr"][i]], dtype=np.int32),
+                 page_indices=c["page_indices"][c["page_indptr"][i]:c["page_indptr"][i + 1]],
+                 row_indptr=np.array([0, 1], dtype=np.int32), verify_len=np.array([1], dtype=np.int32),
+                 q=c["q"][row:row + 1], k_new=c["k_new"][row:row + 1], v_new=c["v_new"][row:row + 1])
+        got, _ = _run(d)
+        np.testing.assert_allclose(got[0], base[row], atol=1e-12)
+    with pytest.raises(ValueError):                                   # more rows than the sequence has
+        oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"], c["page_indices"],
+                              c["kv_len"], c["row_indptr"], [6, 0], page_size=ps)
