@@ -191,6 +191,27 @@ FD_API fd_status fd_accept_sample(const void *target_logits, const void *draft_l
 FD_API size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling);
 
 /*
+ * Commit of the verified rows to the paged KV cache (Sec. 4.3, decoupled execution: the cache
+ * written by target verification is what the next draft step reuses).  Sequence i commits its
+ * anchor row and its first accept_len[i] drafts, i.e. new rows 0 .. accept_len[i] of
+ * args->k_new / v_new; row j is written to logical position kv_len[i] + j (page
+ * page_indices[page_indptr[i] + pos / page_size], slot pos % page_size), so the sequence's
+ * page list must already hold the pages for them.  The bonus token has no K/V yet: it is the
+ * next step's anchor.
+ *   args          the fd_attn_args of the attention call that produced the rows; read here:
+ *                 batch, num_kv_heads, head_dim, page_size, dtype, total_rows, max_new_rows,
+ *                 num_pages, k_cache, v_cache (WRITTEN despite the const), the three strides,
+ *                 page_indptr, page_indices, kv_len, row_indptr, k_new, v_new, status
+ *   accept_len    device int32 [B], 0 <= accept_len[i] < n_i (sequences with n_i = 0 are skipped)
+ *   kv_len_out    device int32 [B]: kv_len[i] + accept_len[i] + 1; may be args->kv_len itself
+ * Out-of-range device data (a page list too short, a page id outside the pool, accept_len out of
+ * range) is skipped or clamped and reported through args->status like in fd_verify_draft_attn.
+ * Asynchronous on hip_stream.  Errors: FD_ERR_INVALID_ARG, FD_ERR_HIP.
+ */
+FD_API fd_status fd_append_kv(const fd_attn_args *args, const int32_t *accept_len, int32_t *kv_len_out,
+                              void *hip_stream);
+
+/*
  * Branch selection of parallel speculative decoding (Sec. 3): the forward pass prepared one
  * candidate block per hypothetical number of accepted drafts; once acceptance has fixed that
  * number, the block drafted under it becomes the next draft.

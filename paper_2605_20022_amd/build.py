@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexdraft.so")
-SOURCES = ["api.hip", "attn_generic.hip", "attn_mfma.hip", "accept.hip", "util.hip"]
+SOURCES = ["api.hip", "attn_generic.hip", "attn_mfma.hip", "accept.hip", "append.hip", "util.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
     "-Wall", "-Wno-unused-result",

@@ -11,6 +11,7 @@ namespace fd {
 hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
 hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int skip_single, hipStream_t st);
 bool attn_mfma_supports(int dtype, int head_dim, int page_size);
+hipError_t run_append_kv(const AttnParams& p, int dtype, const int* accept_len, int* kv_len_out, hipStream_t st);
 hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, const int* mask_blocks,
                              const int* accept_len, const int* first_vis, int batch, int total_tokens,
                              int out_stride, int* out_tokens, int* out_block, hipStream_t st);
@@ -300,6 +301,52 @@ int32_t fd_profile_end(float* ms_out, int32_t capacity) {
   for (int i = 0; i < 2 * g_prof_cap; ++i) (void)hipEventDestroy(g_prof_events[i]);
   delete[] g_prof_events; g_prof_events = nullptr; g_prof_cap = g_prof_used = 0;
   return n;
+}
+
+fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t* kv_len_out, void* hip_stream) {
+  if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
+  if (a->batch < 0 || a->total_rows < 0 || a->max_kv_len < 0 || a->max_new_rows < 0 || a->num_pages < 0)
+    return fail(FD_ERR_INVALID_ARG, "negative size");
+  if (a->num_kv_heads <= 0 || a->head_dim <= 0 || a->head_dim % 8) return fail(FD_ERR_INVALID_ARG, "head_dim %d / num_kv_heads %d", a->head_dim, a->num_kv_heads);
+  if (a->page_size <= 0) return fail(FD_ERR_INVALID_ARG, "page_size %d must be positive", a->page_size);
+  if (a->dtype != FD_F32 && a->dtype != FD_BF16) return fail(FD_ERR_INVALID_ARG, "unknown dtype %d", a->dtype);
+  if (a->batch > 65535) return fail(FD_ERR_UNSUPPORTED, "batch %d > 65535", a->batch);
+  g_err[0] = 0;
+  if (a->batch == 0) return FD_OK;
+  if (!accept_len || !kv_len_out || !a->kv_len || !a->row_indptr || !a->page_indptr || !a->verify_len)
+    return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (a->total_rows == 0 || a->max_new_rows == 0) {
+    // nothing to commit: the lengths are copied
+    if (kv_len_out != a->kv_len &&
+        hipMemcpyAsync(kv_len_out, a->kv_len, sizeof(int32_t) * a->batch, hipMemcpyDeviceToDevice,
+                       reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+      return fail(FD_ERR_HIP, "length copy failed");
+    return FD_OK;
+  }
+  if (!a->k_cache || !a->v_cache || !a->page_indices || !a->k_new || !a->v_new || a->num_pages == 0)
+    return fail(FD_ERR_INVALID_ARG, "k_cache, v_cache, page_indices, k_new, v_new and num_pages > 0 are needed");
+  if (a->cache_stride_page < 0 || a->cache_stride_head < 0 || a->cache_stride_token < a->head_dim ||
+      a->cache_stride_page % 8 || a->cache_stride_head % 8 || a->cache_stride_token % 8)
+    return fail(FD_ERR_INVALID_ARG, "cache strides must be non-negative multiples of 8 elements, token stride >= head_dim");
+  if (!aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->k_cache) || !aligned16(a->v_cache))
+    return fail(FD_ERR_INVALID_ARG, "k_new, v_new, k_cache and v_cache must be 16-byte aligned");
+  if (a->max_new_rows > 65535) return fail(FD_ERR_UNSUPPORTED, "max_new_rows %d > 65535", a->max_new_rows);
+  fd::AttnParams p = {};
+  p.B = a->batch; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads; p.D = a->head_dim;
+  p.G = a->num_kv_heads > 0 && a->num_q_heads > 0 ? a->num_q_heads / a->num_kv_heads : 1;
+  p.page_size = a->page_size;
+  p.total_rows = a->total_rows; p.max_kv_len = a->max_kv_len; p.max_new_rows = a->max_new_rows;
+  p.num_pages = a->num_pages;
+  p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+  p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
+  p.page_indptr = a->page_indptr; p.page_indices = a->page_indices; p.kv_len = a->kv_len;
+  p.row_indptr = a->row_indptr; p.verify_len = a->verify_len; p.mask_vis = a->mask_vis;
+  p.mask_blocks = a->mask_blocks;
+  p.k_new = a->k_new; p.v_new = a->v_new;
+  p.status = a->status;
+  hipError_t e = fd::run_append_kv(p, a->dtype, accept_len, kv_len_out, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "append launch: %s", hipGetErrorString(e));
+  return FD_OK;
 }
 
 fd_status fd_select_branch(const int32_t* block_tokens, const int32_t* block_indptr, const int32_t* mask_blocks,

@@ -50,7 +50,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
+           "fd_accept_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
            "fd_version"]
 
 
@@ -78,6 +78,8 @@ def load() -> C.CDLL:
                                      C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fd_accept_workspace.restype = C.c_size_t
     lib.fd_accept_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.fd_append_kv.restype = C.c_int
+    lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fd_select_branch.restype = C.c_int
     lib.fd_select_branch.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3
     lib.fd_last_error.restype = C.c_char_p
@@ -211,6 +213,12 @@ def fd_profile_end(capacity: int):
     buf = (C.c_float * capacity)()
     n = load().fd_profile_end(buf, capacity)
     return [buf[i] for i in range(n)]
+
+
+def fd_append_kv(args: fd_attn_args, accept_len, kv_len_out, stream=None) -> None:
+    """Commit new rows 0 .. accept_len[i] of the call described by `args` to its paged cache."""
+    _check(load().fd_append_kv(C.byref(args), _ptr(_i32(accept_len, "accept_len")),
+                               _ptr(_i32(kv_len_out, "kv_len_out")), _stream(stream)))
 
 
 def fd_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, out_tokens, *, first_vis=None,
