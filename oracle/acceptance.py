@@ -143,3 +143,38 @@ def accept_sample(target_logits, draft_logits, row_indptr, input_tokens,
         bonus[i] = idx
         r_margin[i] = mg
     return acc, bonus, {"accept_margin": a_margin, "resample_margin": r_margin}
+
+
+def draft_select(draft_logits, row_indptr, temperature: float, threshold: float):
+    """Draft tokens of a mask block, their confidences, and how many of them are worth verifying
+    (Sec. 4.3, selective verification, Eq. 5).
+
+    Row j of a sequence holds the drafter's logits for draft position j+1.  The drafted token is
+    the row's arg-max (lowest index on ties), its confidence p_j the softmax probability of that
+    token at the given temperature, and the chance that the accepted length reaches position i is
+    estimated by the running product p_1 ... p_i.  Positions are kept while that product stays
+    at or above `threshold`; the first one below it, and everything after it, is pruned.  Returns
+    (tokens [R] int32, confidence [R] float64, keep_len [B] int32, margin [B] float64) where
+    margin[i] is the smallest relative distance |product - threshold| / threshold over the
+    comparisons that decided keep_len[i] (inf if the threshold is 0: nothing to decide).
+    """
+    x = to_f64(np.asarray(draft_logits)) / float(temperature)
+    R = x.shape[0]
+    tokens = np.zeros(R, dtype=np.int32)
+    conf = np.zeros(R, dtype=np.float64)
+    for j in range(R):
+        tokens[j] = row_argmax(x[j])
+        conf[j] = softmax64(x[j])[tokens[j]]
+    B = len(row_indptr) - 1
+    keep = np.zeros(B, dtype=np.int32)
+    margin = np.full(B, np.inf)
+    for i in range(B):
+        prod = 1.0
+        for j in range(int(row_indptr[i]), int(row_indptr[i + 1])):
+            prod *= conf[j]
+            if threshold > 0:
+                margin[i] = min(margin[i], abs(prod - threshold) / threshold)
+            if prod < threshold:
+                break
+            keep[i] += 1
+    return tokens, conf, keep, margin

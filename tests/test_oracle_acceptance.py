@@ -245,3 +245,51 @@ def test_empty_sequences_and_margins():
     np.testing.assert_allclose(info["resample_margin"][1], 0.05, atol=1e-12)
     a, b, _ = oc.accept_greedy(xt, [0, 0, 1], [2])
     assert list(a) == [0, 0] and list(b) == [-1, 0]
+
+
+# ---------------------------------------------------------------------------------------
+# Selective verification (Sec. 4.3, Eq. 5): confidence products against a threshold
+# ---------------------------------------------------------------------------------------
+def test_draft_select_closed_form_two_valued_rows():
+    """A row that is `a` at one token and 0 elsewhere has p = e^(a/T) / (e^(a/T) + V - 1)."""
+    V, T = 50, 0.7
+    a = np.array([3.0, 2.0, 4.0, 0.5])
+    pos = [7, 0, 49, 3]
+    x = np.zeros((4, V))
+    for j in range(4):
+        x[j, pos[j]] = a[j]
+    p = np.exp(a / T) / (np.exp(a / T) + V - 1)
+    tok, conf, keep, margin = oc.draft_select(x, [0, 4], T, threshold=p[0] * p[1] * 0.999)
+    assert tok.tolist() == pos
+    np.testing.assert_allclose(conf, p, rtol=1e-13)
+    assert keep.tolist() == [2]                       # p0 p1 >= thr > p0 p1 p2
+    np.testing.assert_allclose(margin[0], 0.001 / 0.999, rtol=1e-9)     # the comparison that kept position 2
+    assert oc.draft_select(x, [0, 4], T, threshold=0.0)[2].tolist() == [4]      # nothing pruned
+    assert oc.draft_select(x, [0, 4], T, threshold=1.1)[2].tolist() == [0]      # everything pruned
+    assert p[1] < p[0] * 0.99
+    assert oc.draft_select(x, [0, 1, 1, 4], T, threshold=p[0] * 0.99)[2].tolist() == [1, 0, 0]   # ragged, one empty
+
+
+def test_draft_select_brute_force_and_ties():
+    rng = np.random.default_rng(12)
+    V = 6
+    x = rng.integers(-2, 3, size=(9, V)).astype(np.float64)          # small integers: plenty of ties
+    indptr = [0, 3, 3, 7, 9]
+    thr = 0.08
+    tok, conf, keep, _ = oc.draft_select(x, indptr, 1.0, thr)
+    for j in range(9):
+        best = max(range(V), key=lambda v: (x[j, v], -v))            # highest value, lowest index
+        assert tok[j] == best
+        z = sum(np.exp(x[j, v]) for v in range(V))
+        assert abs(conf[j] - np.exp(x[j, best]) / z) < 1e-14
+    for i in range(4):
+        prod, n = 1.0, 0
+        for j in range(indptr[i], indptr[i + 1]):
+            prod *= conf[j]
+            if prod < thr:
+                break
+            n += 1
+        assert keep[i] == n
+    uniform = np.zeros((2, 10))
+    t2, c2, k2, _ = oc.draft_select(uniform, [0, 2], 1.0, 0.05)
+    assert t2.tolist() == [0, 0] and np.allclose(c2, 0.1) and k2.tolist() == [1]     # 0.1 >= 0.05 > 0.01
