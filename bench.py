@@ -149,6 +149,34 @@ class Step:
         return res
 
 
+def time_draft_select(fd, torch, batch=32, rows_per_seq=15, vocab=151936, steps=50, copies=4):
+    """fd_draft_select on one step's worth of draft logits (bf16), rotating over several copies of
+    the logits so that no call finds its input in a cache."""
+    from paper_2605_20022_amd import workloads as W
+    R = batch * rows_per_seq
+    lg = [torch.from_numpy(W.make_peaked_logits(vocab, R, seed=c, peak_lo=10.0, peak_hi=20.0).view(np.int16)).cuda().view(torch.bfloat16)
+          for c in range(copies)]
+    ip = torch.arange(0, R + 1, rows_per_seq, dtype=torch.int32, device="cuda")
+    tok = torch.zeros(R, dtype=torch.int32, device="cuda")
+    conf = torch.zeros(R, dtype=torch.float32, device="cuda")
+    keep = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    ws = fd.alloc_workspace(fd.fd_draft_select_workspace(R, vocab))
+    run = lambda i: fd.fd_draft_select(lg[i % copies], ip, tok, keep, temperature=1.0, threshold=0.3,
+                                       max_rows_per_seq=rows_per_seq, confidence=conf, workspace=ws)
+    for i in range(5):
+        run(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i, (s, e) in enumerate(evs):
+        s.record(); run(i); e.record()
+    torch.cuda.synchronize()
+    ts = sorted(s.elapsed_time(e) for s, e in evs)
+    med = ts[len(ts) // 2] * 1e-3
+    nbytes = R * vocab * 2
+    return {"rows": R, "vocab": vocab, "call_us": round(med * 1e6, 2), "logits_GBps": round(nbytes / med / 1e9, 1),
+            "frac_hbm_peak": round(nbytes / med / 1e9 / HBM_PEAK_GBPS, 4), "mean_keep_len": round(float(keep.float().mean()), 2)}
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle, as it stands, on a bounded sample of the same workload: whole sequences are
     added (shortest first would bias; seeded order is used) until about budget_s of CPU time."""
@@ -199,6 +227,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run the library's plain 1 GiB streaming copy (bandwidth yard-stick, counter calibration)")
+    ap.add_argument("--draft-select", action="store_true",
+                    help="only time fd_draft_select (selective verification) on 32 x 15 rows of vocab 151936")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -213,6 +243,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.draft_select:
+        print(json.dumps({"draft_select": time_draft_select(fd, torch, steps=args.steps)}), flush=True)
+        return
     if args.copy_probe:
         n = 1 << 30
         src = torch.ones(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
@@ -277,6 +310,7 @@ def main():
                 per[name]["accept_seqs_per_s"] = round(s2.w.batch / (p2["accept"]["median_ms"] * 1e-3), 1)
             del s2
             torch.cuda.empty_cache()
+        per["draft_select"] = time_draft_select(fd, torch)
         out["per_config"] = per
 
     if not args.no_cpu_baseline:

@@ -191,6 +191,28 @@ FD_API fd_status fd_accept_sample(const void *target_logits, const void *draft_l
 FD_API size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling);
 
 /*
+ * Draft tokens of a mask block and how many of them are worth verifying: selective verification
+ * (Sec. 4.3, Eq. 5) fused with the token pick, one pass over the drafter's logits.
+ *   draft_logits  device [total_rows][vocab] (row stride in elements): row j of a sequence holds
+ *                 the logits of draft position j+1; rows are packed per sequence by row_indptr
+ *   draft_tokens  device int32 [total_rows]: arg-max of each row (lowest index on ties)
+ *   confidence    device float [total_rows] or NULL: p_j = softmax(x_j / temperature)[token]
+ *   keep_len      device int32 [B]: number of leading positions i with p_1 ... p_i >= threshold
+ *                 (the estimate of P(accepted length >= i)); the first position below the
+ *                 threshold and everything after it is pruned.  The next step verifies
+ *                 1 + keep_len[i] rows: the anchor and the kept drafts.
+ * temperature > 0; threshold in [0, 1] is useful (0 keeps everything), any finite value accepted.
+ * Workspace: fd_draft_select_workspace(total_rows, vocab) bytes, device, 256-byte aligned.
+ * Asynchronous on hip_stream.  Errors: FD_ERR_INVALID_ARG, FD_ERR_WORKSPACE_TOO_SMALL, FD_ERR_HIP.
+ */
+FD_API fd_status fd_draft_select(const void *draft_logits, fd_dtype dt, int64_t row_stride, int32_t vocab,
+                                 float temperature, float threshold, const int32_t *row_indptr,
+                                 int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                                 int32_t *draft_tokens, float *confidence, int32_t *keep_len,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+FD_API size_t fd_draft_select_workspace(int32_t total_rows, int32_t vocab);
+
+/*
  * Commit of the verified rows to the paged KV cache (Sec. 4.3, decoupled execution: the cache
  * written by target verification is what the next draft step reuses).  Sequence i commits its
  * anchor row and its first accept_len[i] drafts, i.e. new rows 0 .. accept_len[i] of

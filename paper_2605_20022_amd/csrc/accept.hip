@@ -462,6 +462,129 @@ __global__ __launch_bounds__(ACC_BLOCK) void accept_sample_pick_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Selective verification (Sec. 4.3, Eq. 5), pass 1: per (row, segment) of the drafter's logits the
+// maximum, the lowest index holding it, and the sum of exp((x - max) / T) - the draft token and
+// what its probability needs, in one pass with the segment held in registers.
+//   grid (segments, rows); part_val/part_idx/part_sum [rows][segments]
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ACC_BLOCK) void draft_stats_partial_kernel(
+    const T* __restrict__ logits, long long row_stride, int vocab, int seg_len, float inv_t,
+    float* __restrict__ part_val, int* __restrict__ part_idx, double* __restrict__ part_sum) {
+  const int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
+  const T* rp = logits + (long long)row * row_stride;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(rp) & 15) == 0;
+  const int e0 = seg * seg_len;
+  const int e1 = min(vocab, e0 + min(seg_len, ARG_SEG_MAX));
+  __shared__ float sv[ACC_BLOCK / FD_WAVE]; __shared__ int si[ACC_BLOCK / FD_WAVE];
+  __shared__ double sd[ACC_BLOCK / FD_WAVE];
+  float x[ARG_ROUNDS][8];
+#pragma unroll
+  for (int u = 0; u < ARG_ROUNDS; ++u) load8<T>(rp, e0 + (u * ACC_BLOCK + threadIdx.x) * 8, e1, vec_ok, x[u]);   // -inf past e1
+  float m = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < ARG_ROUNDS; ++u)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(m, x[u][i]);
+  const float wm = wave_max(m);
+  if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = wm;
+  __syncthreads();
+  float M = sv[0];
+#pragma unroll
+  for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) M = fmaxf(M, sv[w]);
+  int bi = 0x7fffffff;
+  float part = 0.f;
+  if (M > -INFINITY) {
+    if (m == M) {                                            // few threads hold the maximum: only they look for it
+#pragma unroll
+      for (int u = ARG_ROUNDS - 1; u >= 0; --u)
+#pragma unroll
+        for (int i = 7; i >= 0; --i)                         // descending walk: the lowest index is kept
+          if (x[u][i] == M) bi = e0 + (u * ACC_BLOCK + threadIdx.x) * 8 + i;   // padding is -inf, never equal
+    }
+    // The terms are summed relative to the segment's maximum, so the term of the maximum is exactly
+    // 1 and every other term's rounding error (|y| * 2^-23 of itself, y = (x - M) / T <= 0) is
+    // weighted by its own small size: the plain hardware exp2 is accurate enough here, and the pass
+    // stays below the cost of the memory traffic.
+    const float c = inv_t * 1.44269502e+00f;
+#pragma unroll
+    for (int u = 0; u < ARG_ROUNDS; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part += __builtin_amdgcn_exp2f((x[u][i] - M) * c);   // padding: 2^-inf = 0
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) bi = min(bi, __shfl_xor(bi, off));
+  const double ws = wave_sum((double)part);
+  if ((threadIdx.x & 63) == 0) { si[threadIdx.x >> 6] = bi; sd[threadIdx.x >> 6] = ws; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < ACC_BLOCK / FD_WAVE; ++w) { bi = min(bi, si[w]); tot += sd[w]; }
+    const long long o = (long long)row * nseg + seg;
+    part_val[o] = M; part_idx[o] = bi; part_sum[o] = tot;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Selective verification, pass 2: one work-group per sequence, DS_GROUP lanes per row, sixteen rows
+// at a time.  A lane group merges its row's segments into the draft token and its probability
+// p = 1 / sum_v exp((x_v - max) / T); thread 0 then walks the rows in order with the running
+// product of the probabilities and counts the positions whose product is still at or above the
+// threshold (Eq. 5); the first one below it ends the count.
+// ---------------------------------------------------------------------------------------
+constexpr int DS_GROUP = 16;
+constexpr int DS_ROWS = ACC_BLOCK / DS_GROUP;
+
+__global__ __launch_bounds__(ACC_BLOCK) void draft_select_epilogue_kernel(
+    const float* __restrict__ part_val, const int* __restrict__ part_idx, const double* __restrict__ part_sum,
+    int nseg, float inv_t, float threshold, const int* __restrict__ row_indptr, int total_rows, int max_rows_per_seq,
+    int* __restrict__ draft_tokens, float* __restrict__ confidence, int* __restrict__ keep_len) {
+  const int seq = blockIdx.x, grp = threadIdx.x / DS_GROUP, gl = threadIdx.x % DS_GROUP;
+  const int r0 = clampi(row_indptr[seq], 0, total_rows);
+  const int k = clampi(row_indptr[seq + 1] - r0, 0, min(max_rows_per_seq, total_rows - r0));
+  __shared__ double s_p[DS_ROWS];
+  double prod = 1.0;
+  int keep = 0;
+  bool open = true;
+  for (int j0 = 0; j0 < k; j0 += DS_ROWS) {                  // k is uniform over the group
+    const int j = min(j0 + grp, k - 1);                      // surplus lane groups repeat the last row, unwritten
+    const long long base = (long long)(r0 + j) * nseg;
+    float m = -INFINITY;
+    for (int s = gl; s < nseg; s += DS_GROUP) m = fmaxf(m, part_val[base + s]);
+#pragma unroll
+    for (int off = DS_GROUP / 2; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    int bi = 0x7fffffff; double z = 0.0;
+    for (int s = gl; s < nseg; s += DS_GROUP) {
+      const float v = part_val[base + s];
+      if (v == m) bi = min(bi, part_idx[base + s]);
+      if (v > -INFINITY) z += part_sum[base + s] * (double)exp_neg((v - m) * inv_t);
+    }
+#pragma unroll
+    for (int off = DS_GROUP / 2; off >= 1; off >>= 1) {
+      bi = min(bi, __shfl_xor(bi, off));
+      z += __shfl_xor(z, off);
+    }
+    const double pj = z > 0.0 ? 1.0 / z : 0.0;
+    if (gl == 0 && j0 + grp < k) {
+      draft_tokens[r0 + j] = bi == 0x7fffffff ? -1 : bi;
+      if (confidence) confidence[r0 + j] = (float)pj;
+      s_p[grp] = pj;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int nrow = min(DS_ROWS, k - j0);
+      for (int i = 0; i < nrow; ++i) {
+        prod *= s_p[i];
+        if (open && prod >= (double)threshold) ++keep; else open = false;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) keep_len[seq] = keep;
+}
+
+// ---------------------------------------------------------------------------------------
 // Branch selection (Sec. 3, parallel speculative decoding): one wave per sequence copies the
 // block drafted under the number of accepted drafts that verification arrived at.
 // ---------------------------------------------------------------------------------------
@@ -590,6 +713,42 @@ static hipError_t launch_sample(const T* target, const T* draft, long long row_s
                        decision, row_stats, chunk_res, chunk_p, accept_len, bonus);
   }
   return hipGetLastError();
+}
+
+size_t draft_select_workspace_bytes(int total_rows, int vocab) {
+  const size_t slots = (size_t)(total_rows > 0 ? total_rows : 1) * pick_segments(total_rows, vocab);
+  return align256(slots * sizeof(float)) + align256(slots * sizeof(int)) + align256(slots * sizeof(double));
+}
+
+template <typename T>
+static hipError_t launch_draft_select(const T* logits, long long row_stride, int vocab, float temperature, float threshold,
+                                      const int* row_indptr, int batch, int total_rows, int max_rows, int* tokens,
+                                      float* confidence, int* keep_len, void* ws, hipStream_t st) {
+  const int nseg = pick_segments(total_rows, vocab);
+  const int sl = seg_len_for(vocab, nseg);
+  const size_t slots = (size_t)(total_rows > 0 ? total_rows : 1) * nseg;
+  char* base = reinterpret_cast<char*>(ws);
+  float* pv = reinterpret_cast<float*>(base);
+  int* pi = reinterpret_cast<int*>(base + align256(slots * sizeof(float)));
+  double* pd = reinterpret_cast<double*>(base + align256(slots * sizeof(float)) + align256(slots * sizeof(int)));
+  const float inv_t = 1.0f / temperature;
+  if (total_rows > 0)
+    hipLaunchKernelGGL(draft_stats_partial_kernel<T>, dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
+                       logits, row_stride, vocab, sl, inv_t, pv, pi, pd);
+  if (batch > 0)
+    hipLaunchKernelGGL(draft_select_epilogue_kernel, dim3(batch), dim3(ACC_BLOCK), 0, st, pv, pi, pd, nseg, inv_t,
+                       threshold, row_indptr, total_rows, max_rows, tokens, confidence, keep_len);
+  return hipGetLastError();
+}
+
+hipError_t run_draft_select(const void* logits, int dt, long long row_stride, int vocab, float temperature,
+                            float threshold, const int* row_indptr, int batch, int total_rows, int max_rows,
+                            int* tokens, float* confidence, int* keep_len, void* ws, hipStream_t st) {
+  if (dt == FD_BF16)
+    return launch_draft_select<bf16_t>((const bf16_t*)logits, row_stride, vocab, temperature, threshold, row_indptr,
+                                       batch, total_rows, max_rows, tokens, confidence, keep_len, ws, st);
+  return launch_draft_select<float>((const float*)logits, row_stride, vocab, temperature, threshold, row_indptr,
+                                    batch, total_rows, max_rows, tokens, confidence, keep_len, ws, st);
 }
 
 hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,

@@ -11,6 +11,10 @@ namespace fd {
 hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
 hipError_t run_attn_combine(const AttnParams& p, int dtype, int log2_units, int skip_single, hipStream_t st);
 bool attn_mfma_supports(int dtype, int head_dim, int page_size);
+size_t draft_select_workspace_bytes(int total_rows, int vocab);
+hipError_t run_draft_select(const void* logits, int dt, long long row_stride, int vocab, float temperature,
+                            float threshold, const int* row_indptr, int batch, int total_rows, int max_rows,
+                            int* tokens, float* confidence, int* keep_len, void* ws, hipStream_t st);
 hipError_t run_append_kv(const AttnParams& p, int dtype, const int* accept_len, int* kv_len_out, hipStream_t st);
 hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, const int* mask_blocks,
                              const int* accept_len, const int* first_vis, int batch, int total_tokens,
@@ -301,6 +305,38 @@ int32_t fd_profile_end(float* ms_out, int32_t capacity) {
   for (int i = 0; i < 2 * g_prof_cap; ++i) (void)hipEventDestroy(g_prof_events[i]);
   delete[] g_prof_events; g_prof_events = nullptr; g_prof_cap = g_prof_used = 0;
   return n;
+}
+
+size_t fd_draft_select_workspace(int32_t total_rows, int32_t vocab) {
+  if (total_rows < 0 || vocab <= 0) return 0;
+  return fd::draft_select_workspace_bytes(total_rows, vocab);
+}
+
+fd_status fd_draft_select(const void* draft_logits, fd_dtype dt, int64_t row_stride, int32_t vocab,
+                          float temperature, float threshold, const int32_t* row_indptr,
+                          int32_t batch, int32_t total_rows, int32_t max_rows_per_seq,
+                          int32_t* draft_tokens, float* confidence, int32_t* keep_len,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (batch < 0 || total_rows < 0 || max_rows_per_seq < 0) return fail(FD_ERR_INVALID_ARG, "negative size");
+  if (vocab <= 0) return fail(FD_ERR_INVALID_ARG, "vocab %d must be positive", vocab);
+  if (dt != FD_F32 && dt != FD_BF16) return fail(FD_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  if (row_stride < vocab) return fail(FD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
+  if (!(temperature > 0.f) || isinf(temperature)) return fail(FD_ERR_INVALID_ARG, "temperature must be finite and > 0");
+  if (isnan(threshold) || isinf(threshold)) return fail(FD_ERR_INVALID_ARG, "threshold must be finite");
+  if (batch > 65535 || total_rows > 65535) return fail(FD_ERR_UNSUPPORTED, "batch %d / total_rows %d > 65535", batch, total_rows);
+  g_err[0] = 0;
+  if (batch == 0) return FD_OK;
+  if (!row_indptr || !keep_len || (total_rows > 0 && (!draft_logits || !draft_tokens)))
+    return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
+  const size_t need = fd::draft_select_workspace_bytes(total_rows, vocab);
+  if (!workspace) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
+  if (workspace_bytes < need) return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", workspace_bytes, need);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  hipError_t e = fd::run_draft_select(draft_logits, dt, row_stride, vocab, temperature, threshold, row_indptr, batch,
+                                      total_rows, max_rows_per_seq, draft_tokens, confidence, keep_len, workspace,
+                                      reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "draft select launch: %s", hipGetErrorString(e));
+  return FD_OK;
 }
 
 fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t* kv_len_out, void* hip_stream) {

@@ -50,7 +50,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
+           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
            "fd_version"]
 
 
@@ -78,6 +78,12 @@ def load() -> C.CDLL:
                                      C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fd_accept_workspace.restype = C.c_size_t
     lib.fd_accept_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.fd_draft_select.restype = C.c_int
+    lib.fd_draft_select.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_float, C.c_float, C.c_void_p,
+                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fd_draft_select_workspace.restype = C.c_size_t
+    lib.fd_draft_select_workspace.argtypes = [C.c_int32, C.c_int32]
     lib.fd_append_kv.restype = C.c_int
     lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fd_select_branch.restype = C.c_int
@@ -213,6 +219,24 @@ def fd_profile_end(capacity: int):
     buf = (C.c_float * capacity)()
     n = load().fd_profile_end(buf, capacity)
     return [buf[i] for i in range(n)]
+
+
+def fd_draft_select_workspace(total_rows: int, vocab: int) -> int:
+    return int(load().fd_draft_select_workspace(total_rows, vocab))
+
+
+def fd_draft_select(draft_logits, row_indptr, draft_tokens, keep_len, *, temperature: float, threshold: float,
+                    max_rows_per_seq: int, confidence=None, vocab=None, workspace, stream=None) -> None:
+    R = draft_logits.shape[0]
+    vocab = draft_logits.shape[1] if vocab is None else vocab
+    if R and draft_logits.stride(1) != 1:
+        raise TypeError("logits rows must be contiguous")
+    _check(load().fd_draft_select(
+        _ptr(draft_logits), _dtype_code(draft_logits), draft_logits.stride(0) if R else vocab, vocab,
+        float(temperature), float(threshold), _ptr(_i32(row_indptr, "row_indptr")), keep_len.shape[0], R,
+        int(max_rows_per_seq), _ptr(_i32(draft_tokens, "draft_tokens")),
+        None if confidence is None else _ptr(confidence), _ptr(_i32(keep_len, "keep_len")),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def fd_append_kv(args: fd_attn_args, accept_len, kv_len_out, stream=None) -> None:

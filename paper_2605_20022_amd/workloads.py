@@ -203,6 +203,19 @@ def make_logits(a: AcceptWorkload, num_rows: int):
     return out
 
 
+def make_peaked_logits(vocab: int, num_rows: int, seed: int, dtype: str = "bf16", peak_lo: float = 6.0,
+                       peak_hi: float = 16.0):
+    """Drafter logits of a mask block: unit-normal background plus one raised entry per row, the
+    raise drawn uniformly from [peak_lo, peak_hi] so that the rows' top probabilities spread from
+    a few percent to nearly one (what the confidence threshold of selective verification sees)."""
+    rng = np.random.default_rng(np.random.PCG64(seed + 4000))
+    x = rng.standard_normal((num_rows, vocab), dtype=np.float32)
+    if num_rows:
+        top = rng.integers(0, vocab, size=num_rows)
+        x[np.arange(num_rows), top] += rng.uniform(peak_lo, peak_hi, size=num_rows).astype(np.float32)
+    return f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
 def make_draft_tokens_agreeing(a: AcceptWorkload, row_indptr: np.ndarray, agree_tokens: np.ndarray):
     """Tokens fed at the verify rows for a greedy workload.
 

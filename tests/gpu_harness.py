@@ -123,6 +123,23 @@ def run_greedy(fd, logits: np.ndarray, row_indptr, tokens, *, vocab=None, want_a
     return acc.cpu().numpy(), bon.cpu().numpy(), (None if am is None else am.cpu().numpy()[:Rv])
 
 
+def run_draft_select(fd, logits: np.ndarray, row_indptr, temperature, threshold, *, vocab=None, want_conf=True):
+    B = len(row_indptr) - 1
+    lg = to_dev(logits)
+    R = lg.shape[0]
+    ip = torch.from_numpy(np.asarray(row_indptr, dtype=np.int32)).cuda()
+    tok = torch.full((max(R, 1),), -7, dtype=torch.int32, device="cuda")
+    conf = torch.full((max(R, 1),), -7.0, dtype=torch.float32, device="cuda") if want_conf else None
+    keep = torch.full((max(B, 1),), -7, dtype=torch.int32, device="cuda")[:B]
+    V = lg.shape[1] if vocab is None else vocab
+    ws = fd.alloc_workspace(fd.fd_draft_select_workspace(R, V))
+    kmax = int(np.diff(row_indptr).max()) if B else 0
+    fd.fd_draft_select(lg, ip, tok, keep, temperature=temperature, threshold=threshold, max_rows_per_seq=kmax,
+                       confidence=conf, vocab=V, workspace=ws)
+    torch.cuda.synchronize()
+    return tok.cpu().numpy()[:R], (None if conf is None else conf.cpu().numpy()[:R]), keep.cpu().numpy()
+
+
 def run_sample(fd, target, draft, row_indptr, tokens, ua, ur, temperature, *, vocab=None):
     B = len(row_indptr) - 1
     tg, dr = to_dev(target), to_dev(draft)

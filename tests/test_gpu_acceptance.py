@@ -11,7 +11,7 @@ import torch
 
 from oracle import acceptance as oc
 from paper_2605_20022_amd import workloads as W
-from tests.gpu_harness import compare_sampling, run_greedy, run_sample
+from tests.gpu_harness import compare_sampling, run_draft_select, run_greedy, run_sample
 
 pytestmark = pytest.mark.gpu
 
@@ -190,3 +190,84 @@ def test_select_branch_matches_oracle(fd):
     for i in range(B):
         if lens[i] % nb[i] == 0:
             assert gb[i] == min(acc[i], nb[i] - 1)
+
+
+# fp32 exponentials carry ~1e-6 relative error on a confidence (the exponent's argument is
+# rounded at magnitude ~20) and a block multiplies up to 15 of them: a product within 1e-4 of
+# the threshold may fall on either side.
+DRAFT_MARGIN = 1e-4
+
+
+def _draft_select_case(fd, logits, indptr, T, thr, **kw):
+    tok, conf, keep = run_draft_select(fd, logits, indptr, T, thr, **kw)
+    V = kw.get("vocab")
+    ref = logits if V is None else logits[:, :V]
+    o_tok, o_conf, o_keep, o_margin = oc.draft_select(ref, indptr, T, thr)
+    assert np.array_equal(tok, o_tok), "draft token differs"
+    if conf is not None:
+        np.testing.assert_allclose(conf, o_conf, rtol=2e-5, atol=1e-30)
+    # the kept length is an integer decided by a float comparison: exact where the oracle's
+    # margin is resolvable in fp32, otherwise the neighbouring length is also a valid outcome
+    firm = o_margin > DRAFT_MARGIN
+    assert np.array_equal(keep[firm], o_keep[firm])
+    if not firm.all():
+        _, _, k_lo, _ = oc.draft_select(ref, indptr, T, thr * (1 + DRAFT_MARGIN))
+        _, _, k_hi, _ = oc.draft_select(ref, indptr, T, thr * (1 - DRAFT_MARGIN))
+        assert np.all((k_lo <= keep) & (keep <= k_hi))
+    return o_tok, o_conf, o_keep
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_draft_select_small_and_edges(fd, dtype):
+    rng = np.random.default_rng(21)
+    for V in (1, 9, 700, 4099, 20000):
+        ks = [0, 1, 7, 3, 0, 15, 2]
+        indptr = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+        lg = W.make_peaked_logits(V, int(indptr[-1]), seed=V, dtype=dtype, peak_lo=2.0, peak_hi=12.0)
+        for T, thr in ((1.0, 0.3), (0.7, 0.05), (1.5, 0.9), (1.0, 0.0), (1.0, 1.5)):
+            _, _, o_keep = _draft_select_case(fd, lg, indptr, T, thr)
+            if thr == 0.0:
+                assert np.array_equal(o_keep, ks)           # nothing pruned
+            if thr > 1.0 and V > 1:
+                assert not o_keep.any()                     # nothing survives
+    # exact ties at the maximum (lowest index wins) and -inf entries
+    vals = rng.integers(-3, 4, size=(12, 513)).astype(np.float32)
+    vals[rng.random(vals.shape) < 0.1] = -np.inf
+    vals[5] = -np.inf; vals[5, 512] = 0.5                   # one finite entry: confidence exactly 1
+    logits = W.f32_to_bf16_bits(vals) if dtype == "bf16" else vals
+    _draft_select_case(fd, logits, [0, 4, 4, 12], 1.0, 0.01)
+    _draft_select_case(fd, logits, [0, 4, 4, 12], 1.0, 0.01, want_conf=False)
+
+
+def test_draft_select_row_stride(fd):
+    lg = W.make_peaked_logits(1003, 6, seed=5, dtype="f32")
+    _draft_select_case(fd, lg, [0, 2, 6], 1.0, 0.2, vocab=1001)
+    _draft_select_case(fd, W.f32_to_bf16_bits(lg), [0, 2, 6], 1.0, 0.2, vocab=990)
+
+
+def test_draft_select_full_vocabulary(fd):
+    """B = 32 blocks of 15 draft positions over the 151 936-entry vocabulary."""
+    indptr = (np.arange(33) * 15).astype(np.int32)
+    lg = W.make_peaked_logits(151936, 480, seed=77, dtype="bf16", peak_lo=10.0, peak_hi=20.0)
+    _, o_conf, o_keep = _draft_select_case(fd, lg, indptr, 1.0, 0.3)
+    assert 0 < o_keep.min() + 1 and o_keep.max() <= 15 and len(set(o_keep.tolist())) > 3
+    assert o_conf.min() < 0.5 < o_conf.max()
+
+
+def test_draft_select_argument_errors(fd):
+    lg = torch.zeros(4, 100, device="cuda")
+    ip = torch.tensor([0, 4], dtype=torch.int32, device="cuda")
+    tok = torch.zeros(4, dtype=torch.int32, device="cuda")
+    keep = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = fd.alloc_workspace(fd.fd_draft_select_workspace(4, 100))
+    kw = dict(max_rows_per_seq=4, workspace=ws)
+    with pytest.raises(fd.FlexDraftError):
+        fd.fd_draft_select(lg, ip, tok, keep, temperature=0.0, threshold=0.3, **kw)
+    with pytest.raises(fd.FlexDraftError):
+        fd.fd_draft_select(lg, ip, tok, keep, temperature=1.0, threshold=float("nan"), **kw)
+    with pytest.raises(fd.FlexDraftError):
+        fd.fd_draft_select(lg, ip, tok, keep, temperature=1.0, threshold=0.3, max_rows_per_seq=4,
+                           workspace=ws[:16])
+    fd.fd_draft_select(lg, ip, tok, keep, temperature=1.0, threshold=0.3, **kw)
+    torch.cuda.synchronize()
+    assert keep.item() == 0 and tok.tolist() == [0, 0, 0, 0]   # uniform rows: p = 1/100 < 0.3
