@@ -219,7 +219,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4", "q3_1p7b", "q3_14b", "q3_32b"])
     ap.add_argument("--all-configs", dest="all_configs", action="store_true", default=True,
                     help="also report every configuration in per_config (default)")
     ap.add_argument("--headline-only", dest="all_configs", action="store_false",
@@ -294,7 +294,7 @@ def main():
 
     if args.all_configs:
         per = {}
-        for name in ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4"]:
+        for name in ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4", "q3_1p7b", "q3_14b", "q3_32b"]:
             s2 = Step(fd, name, torch)
             n = 50
             _, km = s2.timed(n, 5, profile_kernel=True)

@@ -122,6 +122,12 @@ CONFIGS = {
                           seed=BASE_SEED + 5, mask_blocks=0),
              None),
 }
+# The other sizes of the model family the paper decodes with (Sec. 5, models table): cfg3's batch,
+# lengths and paging with the attention shapes of the public Qwen3 configurations.  All of them keep
+# D = 128 and 8 KV heads; what changes is the number of query heads per KV head.
+for _name, _hq in (("q3_1p7b", 16), ("q3_14b", 40), ("q3_32b", 64)):     # 4B shares the 8B shape (32 / 8)
+    CONFIGS[_name] = (AttnWorkload(_name, "bf16", 16, _hq, 8, 128, 16, (512, 4096), (8, 8), 8, _INV_SQRT_128,
+                                   seed=BASE_SEED + 2), None)
 
 
 def make_lengths(w: AttnWorkload):

@@ -67,6 +67,8 @@ def test_generic_kernel_small_cases(fd, case, dtype):
     dict(B=3, G=2, Hkv=2, ps=16, kv=(200, 900), kr=(1, 40), m=40),         # > 64 new rows: two new-row tiles
     dict(B=5, G=4, Hkv=2, ps=16, kv=(1, 130), kr=(1, 16), m=0),            # sequential mode, ragged k
     dict(B=300, G=4, Hkv=1, ps=16, kv=(0, 150), kr=(0, 3), m=2),           # batch larger than one work-group's scan block
+    dict(B=3, G=5, Hkv=2, ps=16, kv=(30, 700), kr=(1, 9), m=8),            # 5 query heads per KV head (not a power of two)
+    dict(B=2, G=3, Hkv=1, ps=16, kv=(0, 260), kr=(0, 30), m=30),           # 3 per KV head, up to 180 tile rows
 ])
 def test_mfma_kernel_small_cases(fd, case):
     w = _wl("small", "bf16", case["B"], case["G"] * case["Hkv"], case["Hkv"], 128, case["ps"], case["kv"],
@@ -188,6 +190,13 @@ def test_cfg3_ragged_paged_batch(fd):
     _check(fd, inp, "bf16", "cfg3")
     sharp = W.make_attention_inputs(w, std=1.0)
     _check(fd, sharp, "bf16", "cfg3 sharp")
+
+
+@pytest.mark.parametrize("name", ["q3_1p7b", "q3_14b", "q3_32b"])
+def test_other_model_shapes(fd, name):
+    """cfg3's ragged paged batch with 2, 5 and 8 query heads per KV head (16, 40, 64 query heads)."""
+    w, _ = W.CONFIGS[name]
+    _check(fd, W.make_attention_inputs(w), "bf16", name)
 
 
 def test_cfg4_large_batch_sequential_sampled(fd):
