@@ -547,11 +547,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
         // visibility + online softmax (base 2) of one block; returns P^T as packed bf16 pairs
         auto softmax_block = [&](f32x16 sc, int kb, unsigned (&pk)[8]) {
           if (masked) {
+            // a prefix tile is the window "keys below the prefix length" (no second range)
+            RowWindow wv = ln.win;
+            if (!is_new) { wv.vr = c1; wv.lo = 0; wv.hi = 0; }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              int key = tile_base + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-              bool vis = is_new ? new_key_visible(ln.win, key) : (key < c1);
-              sc[i] = vis ? sc[i] : -INFINITY;
+              const int key = tile_base + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+              sc[i] = new_key_visible(wv, key) ? sc[i] : -INFINITY;
             }
           }
           float mx = fmaxf(sc[0], sc[1]);
