@@ -187,20 +187,35 @@ def cpu_baseline(name, budget_s=20.0):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    w, _ = W.CONFIGS[name]
+    from oracle import acceptance as oracle_acc
+    w, a = W.CONFIGS[name]
     inp = W.make_attention_inputs(w)
+    lg, indptr = None, None
+    if a is not None:                                   # acceptance leg of the step, one sequence at a time
+        indptr = W.verify_row_indptr(inp)
+        lg = W.make_logits(a, int(indptr[-1]))
     order = np.random.default_rng(0).permutation(w.batch)
     done_bytes, spent, used = 0, 0.0, 0
     for i in order:
         sub = subset_inputs(inp, [int(i)])
         t0 = time.perf_counter()
         oracle_attention(sub)
+        if a is not None:
+            r0, r1 = int(indptr[i]), int(indptr[i + 1])
+            toks = np.zeros(r1 - r0, dtype=np.int32)    # the oracle's cost does not depend on the tokens
+            if a.mode == "greedy":
+                oracle_acc.accept_greedy(lg["target_logits"][r0:r1], [0, r1 - r0], toks)
+            else:
+                oracle_acc.accept_sample(lg["target_logits"][r0:r1], lg["draft_logits"][r0:r1], [0, r1 - r0], toks,
+                                         lg["u_accept"][r0:r1], lg["u_resample"][r0:r1], a.temperature)
         spent += time.perf_counter() - t0
         done_bytes += W.kv_bytes(w, sub["kv_len"]); used += 1
         if spent > budget_s:
             break
+    legs = "oracle attention + acceptance" if a is not None else "oracle attention"
     return dict(value=done_bytes / spent / 1e9, unit="GB/s", cores=int(threads), kind="oracle",
-                sample=f"{used} of {w.batch} sequences of {name} (oracle attention only), {spent:.1f} s")
+                sample=f"{used} of {w.batch} sequences of {name} ({legs}; the whole step when all sequences fit "
+                       f"the {budget_s:.0f} s budget), {spent:.1f} s")
 
 
 def read_traffic(name):
