@@ -189,72 +189,68 @@ __device__ __forceinline__ float exp_neg(float y) {
   return fmaf(e, r * 0.693147182f, e);
 }
 
-// One streaming pass with a running maximum: (m, s) with s = sum exp(x*invT - m), rescaled
-// whenever the maximum grows; thread results are merged the same way.
-template <typename T>
-__device__ __forceinline__ void segment_max_sum(const T* rp, int e0, int e1, float inv_t, bool vec_ok,
-                                                float* s_red, double* d_red, double& out_max, double& out_sum) {
-  float m = -INFINITY; double s = 0.0;
-  for (int e = e0 + threadIdx.x * 8; e < e1; e += ACC_BLOCK * 8) {
-    float x[8]; load8<T>(rp, e, e1, vec_ok, x);
-    float m8 = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { x[i] *= inv_t; m8 = fmaxf(m8, x[i]); }   // padding stays -inf (invT > 0)
-    if (m8 > m) { s *= (double)exp_neg(m - m8); m = m8; }
-    if (m > -INFINITY) {
-      float part = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) part += exp_neg(x[i] - m);
-      s += (double)part;
-    }
-  }
-  const float wm = wave_max(m);
-  double ws = (m > -INFINITY) ? s * (double)exp_neg(m - wm) : 0.0;
-  ws = wave_sum(ws);
-  if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = wm; d_red[threadIdx.x >> 6] = ws; }
-  __syncthreads();
-  float bm = s_red[0];
-  for (int w = 1; w < ACC_BLOCK / FD_WAVE; ++w) bm = fmaxf(bm, s_red[w]);
-  double bs = 0.0;
-  for (int w = 0; w < ACC_BLOCK / FD_WAVE; ++w)
-    if (s_red[w] > -INFINITY) bs += d_red[w] * (double)exp_neg(s_red[w] - bm);
-  __syncthreads();
-  out_max = (double)bm; out_sum = bs;
-}
-
-template <typename T>
+// Sampling, pass 1: per (row, segment) the maximum of x / T and sum exp(x / T - max), for the
+// target and the draft logits.  Both segments are requested up front and held in registers (one
+// memory latency per work-group), the maximum is found first and the sum taken relative to it: the
+// maximum's own term is exactly 1 and every other term's rounding error (|y| 2^-23 of itself,
+// y = x / T - max <= 0) is weighted by its small size, so the plain hardware exp2 is accurate
+// enough for a normaliser that is compared at 1e-5.
+//   grid (segments, rows); part [rows][segments][4] = (max_t, sum_t, max_d, sum_d)
+//   NR = rounds of ACC_BLOCK * 8 logits that cover a segment (registers held: 16 NR floats)
+template <typename T, int NR>
 __global__ __launch_bounds__(ACC_BLOCK) void softmax_stats_partial_kernel(
     const T* __restrict__ target, const T* __restrict__ draft, long long row_stride, int vocab, int seg_len,
     float inv_t, double* __restrict__ part) {
-  __shared__ float s_red[ACC_BLOCK / FD_WAVE]; __shared__ double d_red[ACC_BLOCK / FD_WAVE];
+  constexpr int NW = ACC_BLOCK / FD_WAVE;
+  __shared__ float s_max[2][NW]; __shared__ double s_sum[2][NW];
   const int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
-  const int e0 = seg * seg_len, e1 = min(vocab, e0 + seg_len);
+  const int e0 = seg * seg_len, e1 = min(vocab, e0 + min(seg_len, NR * ACC_BLOCK * 8));
   const T* tp = target + (long long)row * row_stride;
   const T* dp = draft + (long long)row * row_stride;
-  double mt, st, md, sd;
-  segment_max_sum<T>(tp, e0, e1, inv_t, (reinterpret_cast<uintptr_t>(tp) & 15) == 0, s_red, d_red, mt, st);
-  segment_max_sum<T>(dp, e0, e1, inv_t, (reinterpret_cast<uintptr_t>(dp) & 15) == 0, s_red, d_red, md, sd);
-  if (threadIdx.x == 0) {
-    double* o = part + ((long long)row * nseg + seg) * 4;
-    o[0] = mt; o[1] = st; o[2] = md; o[3] = sd;
-  }
-}
-
-// Merge the segment statistics of one row (all lanes of a wave take part): returns the
-// row maximum M (scaled units) and Z = sum exp(x*invT - M), for target (0) or draft (2).
-__device__ __forceinline__ void merge_row_stats(const double* part_row, int nseg, int which, int lane,
-                                                double& M, double& Z) {
-  double m = -INFINITY;
-  for (int s = lane; s < nseg; s += FD_WAVE) m = fmax(m, part_row[s * 4 + which]);
+  const bool vt = (reinterpret_cast<uintptr_t>(tp) & 15) == 0, vd = (reinterpret_cast<uintptr_t>(dp) & 15) == 0;
+  float xt[NR][8], xd[NR][8];
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) m = fmax(m, __shfl_xor(m, off));
-  double z = 0.0;
-  for (int s = lane; s < nseg; s += FD_WAVE) {
-    double ms = part_row[s * 4 + which], ss = part_row[s * 4 + which + 1];
-    if (ss > 0.0) z += ss * (double)exp_neg((float)(ms - m));      // maxima are floats held in doubles: the difference is exact
+  for (int u = 0; u < NR; ++u) load8<T>(tp, e0 + (u * ACC_BLOCK + threadIdx.x) * 8, e1, vt, xt[u]);   // -inf past e1
+#pragma unroll
+  for (int u = 0; u < NR; ++u) load8<T>(dp, e0 + (u * ACC_BLOCK + threadIdx.x) * 8, e1, vd, xd[u]);
+  float mt = -INFINITY, md = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < NR; ++u)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      xt[u][i] *= inv_t; xd[u][i] *= inv_t;                       // padding stays -inf (1 / T > 0)
+      mt = fmaxf(mt, xt[u][i]); md = fmaxf(md, xd[u][i]);
+    }
+  mt = wave_max(mt); md = wave_max(md);
+  if ((threadIdx.x & 63) == 0) { s_max[0][threadIdx.x >> 6] = mt; s_max[1][threadIdx.x >> 6] = md; }
+  __syncthreads();
+  float Mt = s_max[0][0], Md = s_max[1][0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { Mt = fmaxf(Mt, s_max[0][w]); Md = fmaxf(Md, s_max[1][w]); }
+  float st = 0.f, sd = 0.f;
+  const float L2E = 1.44269502e+00f;
+  if (Mt > -INFINITY) {
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) st += __builtin_amdgcn_exp2f((xt[u][i] - Mt) * L2E);     // padding: 2^-inf = 0
   }
-  z = wave_sum(z);
-  M = m; Z = z;
+  if (Md > -INFINITY) {
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sd += __builtin_amdgcn_exp2f((xd[u][i] - Md) * L2E);
+  }
+  const double wt = wave_sum((double)st), wd = wave_sum((double)sd);
+  if ((threadIdx.x & 63) == 0) { s_sum[0][threadIdx.x >> 6] = wt; s_sum[1][threadIdx.x >> 6] = wd; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tt = 0.0, td = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { tt += s_sum[0][w]; td += s_sum[1][w]; }
+    double* o = part + ((long long)row * nseg + seg) * 4;
+    o[0] = (double)Mt; o[1] = tt; o[2] = (double)Md; o[3] = td;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -282,42 +278,58 @@ __global__ __launch_bounds__(ACC_BLOCK) void accept_sample_weights_kernel(
   int k = clampi(row_indptr[seq + 1] - r0, 0, min(max_rows_per_seq, total_rows - r0));
   if (k == 0) { if (grp == 0 && threadIdx.x == 0) { decision[seq * 4] = -1; decision[seq * 4 + 1] = 0; } return; }
 
+  // Accept tests: SG lanes per row merge that row's segment statistics, ROWS_AT_ONCE rows at a time
+  // (every load of a batch is in flight together).  The statistics of a batch stay in LDS, so the
+  // row the step stops at -- the first rejected draft, else the last row -- is at hand afterwards.
+  constexpr int SG = 16, ROWS_AT_ONCE = ACC_BLOCK / SG;
   __shared__ int s_first_bad;
+  __shared__ double s_rows[ROWS_AT_ONCE][4];
   __shared__ double s_stats[4];
+  const int grp16 = threadIdx.x / SG, gl = threadIdx.x % SG;
   if (threadIdx.x == 0) s_first_bad = k - 1;
   __syncthreads();
-  // accept tests, rows distributed over the waves; every wave evaluates whole rows
-  for (int j = wave; j < k - 1; j += NW) {
-    if (j > *(volatile int*)&s_first_bad) break;      // monotone shortcut: later rows cannot matter
+  int stop = k - 1;
+  for (int j0 = 0; j0 < k; j0 += ROWS_AT_ONCE) {
+    const int j = min(j0 + grp16, k - 1);                          // surplus lane groups repeat the last row
     const double* pr = part + (long long)(r0 + j) * nseg * 4;
-    double Mt, Zt, Md, Zd;
-    merge_row_stats(pr, nseg, 0, lane, Mt, Zt);
-    merge_row_stats(pr, nseg, 2, lane, Md, Zd);
-    if (lane == 0) {
-      int d = input_tokens[r0 + j + 1];
-      bool keep = false;
-      if (d >= 0 && d < vocab) {
-        float xt = Elem<T>::load(target + (long long)(r0 + j) * row_stride + d);
-        float xd = Elem<T>::load(draft + (long long)(r0 + j) * row_stride + d);
-        double p = (double)expf(xt * inv_t - (float)Mt) / Zt;
-        double q = (double)expf(xd * inv_t - (float)Md) / Zd;
-        keep = (double)u_accept[r0 + j] * q < p;
-      }
-      if (!keep) atomicMin(&s_first_bad, j);
+    double mt = -INFINITY, md = -INFINITY;
+    for (int sg = gl; sg < nseg; sg += SG) { mt = fmax(mt, pr[sg * 4]); md = fmax(md, pr[sg * 4 + 2]); }
+#pragma unroll
+    for (int off = SG / 2; off >= 1; off >>= 1) { mt = fmax(mt, __shfl_xor(mt, off)); md = fmax(md, __shfl_xor(md, off)); }
+    double zt = 0.0, zd = 0.0;
+    for (int sg = gl; sg < nseg; sg += SG) {
+      const double m0 = pr[sg * 4], s0 = pr[sg * 4 + 1], m1 = pr[sg * 4 + 2], s1 = pr[sg * 4 + 3];
+      if (s0 > 0.0) zt += s0 * (double)exp_neg((float)(m0 - mt));     // maxima are floats held in doubles: the difference is exact
+      if (s1 > 0.0) zd += s1 * (double)exp_neg((float)(m1 - md));
     }
+#pragma unroll
+    for (int off = SG / 2; off >= 1; off >>= 1) { zt += __shfl_xor(zt, off); zd += __shfl_xor(zd, off); }
+    if (gl == 0 && j0 + grp16 < k) {
+      s_rows[grp16][0] = mt; s_rows[grp16][1] = zt; s_rows[grp16][2] = md; s_rows[grp16][3] = zd;
+      if (j < k - 1) {                                              // the last row has no draft to test
+        const int d = input_tokens[r0 + j + 1];
+        bool keep = false;
+        if (d >= 0 && d < vocab) {
+          const float xt = Elem<T>::load(target + (long long)(r0 + j) * row_stride + d);
+          const float xd = Elem<T>::load(draft + (long long)(r0 + j) * row_stride + d);
+          const double p = (double)expf(xt * inv_t - (float)mt) / zt;
+          const double q = (double)expf(xd * inv_t - (float)md) / zd;
+          keep = (double)u_accept[r0 + j] * q < p;
+        }
+        if (!keep) atomicMin(&s_first_bad, j);
+      }
+    }
+    __syncthreads();
+    stop = s_first_bad;
+    if (stop < j0 + ROWS_AT_ONCE) {                                 // the stopping row is in this batch
+      if (threadIdx.x < 4) s_stats[threadIdx.x] = s_rows[stop - j0][threadIdx.x];
+      break;                                                        // (uniform: every thread read the same stop)
+    }
+    __syncthreads();                                                // s_rows is rewritten by the next batch
   }
   __syncthreads();
-  const int stop = s_first_bad;
   const bool rejected = stop < k - 1 ? true : false;   // stop == k-1 only when every draft was kept
   // (a rejection at row k-1 cannot happen: that row has no draft to test)
-  if (wave == 0) {
-    const double* pr = part + (long long)(r0 + stop) * nseg * 4;
-    double Mt, Zt, Md, Zd;
-    merge_row_stats(pr, nseg, 0, lane, Mt, Zt);
-    merge_row_stats(pr, nseg, 2, lane, Md, Zd);
-    if (lane == 0) { s_stats[0] = Mt; s_stats[1] = Zt; s_stats[2] = Md; s_stats[3] = Zd; }
-  }
-  __syncthreads();
   const float Mt = (float)s_stats[0], Md = (float)s_stats[2];
   const double iZt = 1.0 / s_stats[1], iZd = 1.0 / s_stats[3];
   if (grp == 0 && threadIdx.x == 0) {
@@ -620,17 +632,18 @@ hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, c
 // host-side launchers (called from api.hip)
 // ---------------------------------------------------------------------------------------
 static inline int pick_segments(int rows, int vocab) {
-  // enough work-groups to cover the chip a few times, but at least 4096 logits per group, and
-  // never more logits per group than the arg-max pass holds in registers
+  // Around 2048 work-groups in all, each taking a whole number of rounds (ACC_BLOCK * 8 logits, one
+  // 16-byte load per lane): at least two rounds, so that a group has 4096 logits to work on, and
+  // never more than the passes hold in registers.
   int want = (2048 + rows - 1) / (rows > 0 ? rows : 1);
-  int cap = (vocab + 4095) / 4096;
-  int s = want < 1 ? 1 : want;
-  if (s > cap) s = cap;
-  if (s > 64) s = 64;
-  int need = (vocab + ARG_SEG_MAX - 1) / ARG_SEG_MAX;
-  if (s < need) s = need;
-  if (s < 1) s = 1;
-  return s;
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  const long long round_len = (long long)ACC_BLOCK * 8;
+  long long r = (vocab + want * round_len - 1) / (want * round_len);
+  if (r < 2) r = 2;
+  if (r > ARG_ROUNDS) r = ARG_ROUNDS;
+  long long s = (vocab + r * round_len - 1) / (r * round_len);
+  return (int)(s < 1 ? 1 : s);
 }
 static inline int seg_len_for(int vocab, int nseg) {
   int l = (vocab + nseg - 1) / nseg;
@@ -698,8 +711,15 @@ static hipError_t launch_sample(const T* target, const T* draft, long long row_s
   int* decision = reinterpret_cast<int*>(base + lay.decision);
   float inv_t = 1.0f / temperature;
   if (total_rows > 0)
-    hipLaunchKernelGGL(softmax_stats_partial_kernel<T>, dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
-                       target, draft, row_stride, vocab, sl, inv_t, part);
+    switch ((sl + ACC_BLOCK * 8 - 1) / (ACC_BLOCK * 8)) {        // rounds that cover a segment (<= ARG_ROUNDS)
+#define FD_STATS_CASE(NR)                                                                                          \
+      case NR: hipLaunchKernelGGL((softmax_stats_partial_kernel<T, NR>), dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st, \
+                                  target, draft, row_stride, vocab, sl, inv_t, part); break;
+      FD_STATS_CASE(1) FD_STATS_CASE(2) FD_STATS_CASE(3) FD_STATS_CASE(4)
+      default: hipLaunchKernelGGL((softmax_stats_partial_kernel<T, ARG_ROUNDS>), dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
+                                  target, draft, row_stride, vocab, sl, inv_t, part); break;
+#undef FD_STATS_CASE
+    }
   if (batch > 0) {
     int groups = (nchunks + (ACC_BLOCK / FD_WAVE) - 1) / (ACC_BLOCK / FD_WAVE);
     int want = (1024 + batch - 1) / batch;
