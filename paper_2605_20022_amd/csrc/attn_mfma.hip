@@ -244,8 +244,10 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
   }
 
-  const int ld_key = tid >> 4;                 // 0..15: key within a 16-key group
-  const int ld_col = (tid & 15) * 8;           // element offset of this thread's 16 bytes
+  // Tile loads: wave w fetches the w-th 16-key group of a tile (one page: one base address, one pair
+  // of buffer descriptors per wave and tile); lane l takes 16-byte column l & 15 of keys (l >> 4) + 4 i.
+  const int ld_row = lane >> 4;                // 0..3
+  const int ld_col = (lane & 15) * 8;          // element offset of this lane's 16 bytes
   const int page_mask = p.page_size - 1;
   const float cs = p.sm_scale * 1.4426950408889634f;           // scores are kept in base-2 units
 
@@ -311,9 +313,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     return false;
   };
 
-  const unsigned lane_boff = (unsigned)(2 * ((long long)ld_key * p.st + ld_col));       // bytes within a cached 16-key slab
+  unsigned voff_c[4], voff_n[4];               // byte offsets of this lane's four rows in a cached / a new 16-key group
   const long long new_pitch = (long long)p.Hkv * MF_D;
-  const unsigned lane_off_new = (unsigned)(2 * ((long long)ld_key * new_pitch + ld_col)); // bytes within 16 new rows
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    voff_c[i] = (unsigned)(2 * ((long long)(ld_row + 4 * i) * p.st + ld_col));
+    voff_n[i] = (unsigned)(2 * ((long long)(ld_row + 4 * i) * new_pitch + ld_col));
+  }
 
   // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
   // fetched with scalar loads ahead of time and range-checked when the addresses are formed.
@@ -340,11 +346,14 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
   // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows past the
   // descriptor's size read as zero.  `nrec` = bytes from the base to the end of the last valid row.
-  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, unsigned lane_off, u32x4& rk, u32x4& rv) {
+  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, const unsigned (&voff)[4], TileRegs& r) {
     __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
     __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
-    rk = __builtin_amdgcn_raw_buffer_load_b128(rk_, lane_off, 0, 2);      // aux 2: streaming (nt)
-    rv = __builtin_amdgcn_raw_buffer_load_b128(rv_, lane_off, 0, 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 2);      // aux 2: streaming (nt)
+      r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 2);
+    }
   };
   auto nrec_of = [&](int valid, unsigned pitch) -> int {                 // valid rows of a 16-row group
     const int v16 = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
@@ -355,50 +364,30 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   const unsigned sp32 = (unsigned)p.sp, st32 = (unsigned)p.st;
   const int nrec_full = (int)((15u * st32 + MF_D) * 2u);
   auto load_tile = [&](const Piece& pc, int tau, const int (&pg)[MF_GROUPS], TileRegs& r) {
+    const int gi = __builtin_amdgcn_readfirstlane(wave);   // this wave's 16-key group of the tile
     if (tau < pc.n_ct_all) {
-      const int base = tau * MF_TK;
-      unsigned bad = 0;
-      if (base + MF_TK <= pc.s.L) {                 // every key of the tile is valid: the usual case
-#pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j) {
-          unsigned ph = (unsigned)pg[j];
-          const unsigned oob = ph >= (unsigned)p.num_pages ? 1u : 0u;
-          bad |= oob;
-          ph = oob ? 0u : ph;
-          const unsigned long long ub = (unsigned long long)ph * sp32 + (unsigned)((base + 16 * j) & page_mask) * st32;
-          load_rows(pc.kh + ub, pc.vh + ub, nrec_full, lane_boff, r.k[j], r.v[j]);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < MF_GROUPS; ++j) {
-          const int gs = base + 16 * j;
-          unsigned ph = (unsigned)pg[j];
-          const unsigned oob = ph >= (unsigned)p.num_pages ? 1u : 0u;
-          bad |= oob & (gs < pc.s.L ? 1u : 0u);
-          ph = oob ? 0u : ph;
-          const unsigned long long ub = (unsigned long long)ph * sp32 + (unsigned)(gs & page_mask) * st32;
-          load_rows(pc.kh + ub, pc.vh + ub, nrec_of(pc.s.L - gs, st32), lane_boff, r.k[j], r.v[j]);
-        }
-      }
-      if (bad) flag_status(p.status, FD_DEV_PAGE_RANGE);
+      const int gs = tau * MF_TK + 16 * gi;
+      unsigned ph = (unsigned)(gi == 0 ? pg[0] : gi == 1 ? pg[1] : gi == 2 ? pg[2] : pg[3]);
+      const unsigned oob = ph >= (unsigned)p.num_pages ? 1u : 0u;
+      if (oob & (gs < pc.s.L ? 1u : 0u)) flag_status(p.status, FD_DEV_PAGE_RANGE);
+      ph = oob ? 0u : ph;
+      const unsigned long long ub = (unsigned long long)ph * sp32 + (unsigned)(gs & page_mask) * st32;
+      const int nrec = gs + 16 <= pc.s.L ? nrec_full : nrec_of(pc.s.L - gs, st32);   // rows past the prefix read as zero
+      load_rows(pc.kh + ub, pc.vh + ub, nrec, voff_c, r);
     } else {
-      const int base = (tau - pc.n_ct_all) * MF_TK;
-#pragma unroll
-      for (int j = 0; j < MF_GROUPS; ++j) {
-        const int key0 = base + 16 * j;
-        const long long ub = ((long long)(pc.s.row0 + key0) * p.Hkv + pc.head) * MF_D;
-        load_rows(Kn + ub, Vn + ub, nrec_of(pc.s.n - key0, (unsigned)new_pitch), lane_off_new, r.k[j], r.v[j]);
-      }
+      const int key0 = (tau - pc.n_ct_all) * MF_TK + 16 * gi;
+      const long long ub = ((long long)(pc.s.row0 + key0) * p.Hkv + pc.head) * MF_D;
+      load_rows(Kn + ub, Vn + ub, nrec_of(pc.s.n - key0, (unsigned)new_pitch), voff_n, r);
     }
   };
   auto store_tile = [&](int buf, const TileRegs& r) {
     bf16_t* Kb = lds + buf * MF_BUF_ELEMS;
     bf16_t* Vb = Kb + MF_K_ELEMS;
 #pragma unroll
-    for (int j = 0; j < MF_GROUPS; ++j) {
-      int row = 16 * j + ld_key;
-      *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[j];
-      *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[j];
+    for (int i = 0; i < 4; ++i) {
+      const int row = 16 * wave + ld_row + 4 * i;
+      *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[i];
+      *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[i];
     }
   };
 
