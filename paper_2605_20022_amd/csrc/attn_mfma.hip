@@ -40,6 +40,15 @@
 #include "fd_common.h"
 #include <type_traits>
 
+// MFMAs by which the LDS fragment requests of S = K Q^T and O += V^T P^T run ahead of their use
+// (3 and 3: measured best of 2..4; more costs registers the 64-row variant does not have)
+#ifndef FD_PF_K
+#define FD_PF_K 3
+#endif
+#ifndef FD_PF_V
+#define FD_PF_V 3
+#endif
+
 namespace fd {
 
 constexpr int MF_BLOCK = 256;
@@ -115,6 +124,7 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 template <int DBG, int MAXRB>
 __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int PF_K = FD_PF_K, PF_V = FD_PF_V;   // LDS fragment requests run this many MFMAs ahead
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   __shared__ int sh_w[MF_BLOCK / 64];
   __shared__ int sh_found[12];
@@ -526,10 +536,16 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
           for (int i = 0; i < 16; ++i) sc[i] = 0.f;
           const bf16_t* kp = Ks + (32 * kb + c32) * MF_KSTR + 8 * h;
+          // K fragments are requested PF_K MFMAs before the MFMA that consumes them
+          u32x4 kf[8];
+#pragma unroll
+          for (int f = 0; f < PF_K; ++f) kf[f] = *reinterpret_cast<const u32x4*>(kp + 16 * f);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int st = 0; st < 8; ++st) {
-            bf16x8 kf = as_bf16x8(*reinterpret_cast<const u32x4*>(kp + 16 * st));
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sc, 0, 0, 0);
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[st]), qf[st], sc, 0, 0, 0);
+            if (st + PF_K < 8) kf[st + PF_K] = *reinterpret_cast<const u32x4*>(kp + 16 * (st + PF_K));
+            __builtin_amdgcn_sched_barrier(0);                     // keep the requests where they are written
           }
           return sc;
         };
@@ -571,19 +587,25 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
         };
         // O^T += V^T P^T for block kb
         auto compute_PV = [&](int kb, const unsigned (&pk)[8]) {
+          // V^T fragment pair g: d-block g % 4 of k-step g / 4; keys of a k-step for lane-half h are
+          // base+4h+{0..3} and base+8+4h+{0..3}.  Pairs are requested PF_V MFMAs ahead.
+          const bf16_t* vbase = Vs + (32 * kb + 4 * h + (l16 >> 2)) * MF_VSTR + 16 * (c32 >> 4) + 4 * (l16 & 3);
+          s16x4 vf[16];
+          auto vread = [&](int g) {
+            const bf16_t* vp = vbase + 16 * (g >> 2) * MF_VSTR + 32 * (g & 3);
+            vf[2 * g] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)vp);
+            vf[2 * g + 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * MF_VSTR));
+          };
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            u32x4 pw = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
-            const bf16x8 pf = as_bf16x8(pw);
-            // keys of this k-step for lane-half h: base+4h+{0..3} and base+8+4h+{0..3}
-            const bf16_t* vp = Vs + (32 * kb + 16 * j + 4 * h + (l16 >> 2)) * MF_VSTR + 16 * (c32 >> 4) + 4 * (l16 & 3);
+          for (int g = 0; g < PF_V; ++g) vread(g);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-              s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b));
-              s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * b + 8 * MF_VSTR));
-              s16x8 vv = {v1[0], v1[1], v1[2], v1[3], v2[0], v2[1], v2[2], v2[3]};
-              o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o[b], 0, 0, 0);
-            }
+          for (int g = 0; g < 8; ++g) {
+            const int q = g >> 2;
+            u32x4 pw = {pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]};
+            s16x8 vv = {vf[2 * g][0], vf[2 * g][1], vf[2 * g][2], vf[2 * g][3],
+                        vf[2 * g + 1][0], vf[2 * g + 1][1], vf[2 * g + 1][2], vf[2 * g + 1][3]};
+            o[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), as_bf16x8(pw), o[g & 3], 0, 0, 0);
+            if (g + PF_V < 8) vread(g + PF_V);
           }
         };
         auto run_blocks = [&](auto nblk_c, int stride) {
