@@ -115,6 +115,30 @@ class Step:
             self.accept()
         self.i += 1
 
+    def time_append(self, steps=50):
+        """fd_append_kv (commit of the anchor and the accepted drafts) on this workload.  The call is
+        given lengths 16 below the real ones, so that every page list has room for the committed rows
+        (they overwrite the last cached tokens of the pools: run this after everything else)."""
+        torch = self.torch
+        B = self.w.batch
+        rng = np.random.default_rng(7)
+        acc = torch.from_numpy(np.array([rng.integers(0, max(int(k), 1)) for k in self.inp["verify_len"]], dtype=np.int32)).cuda()
+        short = (self.call.d["kv_len"] - 16).clamp_(min=0)
+        out_len = torch.zeros(B, dtype=torch.int32, device="cuda")
+        args = []
+        for a in self.attn_args:
+            b = self.fd.fd_attn_args.from_buffer_copy(a); b.kv_len = short.data_ptr(); args.append(b)
+        for i in range(5):
+            self.fd.fd_append_kv(args[i % len(args)], acc, out_len)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for i, (s, e) in enumerate(evs):
+            s.record(); self.fd.fd_append_kv(args[i % len(args)], acc, out_len); e.record()
+        torch.cuda.synchronize()
+        ts = sorted(s.elapsed_time(e) for s, e in evs)
+        rows = int((acc + 1).sum().item())
+        return {"append_us": round(ts[len(ts) // 2] * 1e3, 2), "append_rows": rows}
+
     def timed(self, steps, warmup, profile_kernel=False):
         torch = self.torch
         for _ in range(warmup):
@@ -175,6 +199,25 @@ def time_draft_select(fd, torch, batch=32, rows_per_seq=15, vocab=151936, steps=
     nbytes = R * vocab * 2
     return {"rows": R, "vocab": vocab, "call_us": round(med * 1e6, 2), "logits_GBps": round(nbytes / med / 1e9, 1),
             "frac_hbm_peak": round(nbytes / med / 1e9 / HBM_PEAK_GBPS, 4), "mean_keep_len": round(float(keep.float().mean()), 2)}
+
+
+def time_select_branch(fd, torch, batch=128, blocks=16, block_len=15, steps=50):
+    """fd_select_branch: per sequence, keep the candidate block drafted under the accepted count."""
+    B, nb, mb = batch, blocks, block_len
+    toks = torch.randint(0, 151936, (B * nb * mb,), dtype=torch.int32, device="cuda")
+    indptr = torch.arange(0, B * nb * mb + 1, nb * mb, dtype=torch.int32, device="cuda")
+    nblocks = torch.full((B,), nb, dtype=torch.int32, device="cuda")
+    acc = torch.randint(0, nb, (B,), dtype=torch.int32, device="cuda")
+    out = torch.zeros(B, mb, dtype=torch.int32, device="cuda")
+    for _ in range(5):
+        fd.fd_select_branch(toks, indptr, nblocks, acc, out)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for s, e in evs:
+        s.record(); fd.fd_select_branch(toks, indptr, nblocks, acc, out); e.record()
+    torch.cuda.synchronize()
+    ts = sorted(s.elapsed_time(e) for s, e in evs)
+    return {"batch": B, "blocks": nb, "block_len": mb, "call_us": round(ts[len(ts) // 2] * 1e3, 2)}
 
 
 def cpu_baseline(name, budget_s=20.0):
@@ -323,9 +366,12 @@ def main():
             if "accept" in p2:
                 per[name]["accept_us"] = round(p2["accept"]["median_ms"] * 1e3, 2)
                 per[name]["accept_seqs_per_s"] = round(s2.w.batch / (p2["accept"]["median_ms"] * 1e-3), 1)
+            if name in ("cfg3", "cfg4"):
+                per[name].update(s2.time_append(n))
             del s2
             torch.cuda.empty_cache()
         per["draft_select"] = time_draft_select(fd, torch)
+        per["select_branch"] = time_select_branch(fd, torch)
         out["per_config"] = per
 
     if not args.no_cpu_baseline:
