@@ -728,22 +728,23 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 // Merge the split partials of every item that was cut by a share boundary:
 //   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
 // The pieces of an item sit in its first slot, then in the first slot (2w) of every later
-// work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 4):
-// one wave per tile row, a lane owns two adjacent output columns.
+// work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 8):
+// half a wave per tile row, a lane owns four adjacent output columns.
 // ---------------------------------------------------------------------------------------
 template <int MAXRB>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
-  typedef __attribute__((ext_vector_type(2))) float f32x2;
   const int wl = blockIdx.x;                      // the work-group in which the split item ended
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31;                      // a half-wave owns a tile row, a lane four adjacent output columns
   const int* ep = reinterpret_cast<const int*>(sc_.entries + wl);
   const int row0 = sload(ep, 0), head_rt = sload(ep, 1), rows_here = sload(ep, 2), first_slot = sload(ep, 3);
   if (row0 < 0) return;
-  const int trow = blockIdx.y * 4 + wave;
+  const int trow = blockIdx.y * 8 + wave * 2 + (lane >> 5);
   const int head = head_rt & 0xffff, rt = head_rt >> 16;
   const int wf = first_slot >> 1;
-  if (trow >= rows_here || rows_here > ROWS_WG || first_slot < 0 || wf >= wl || head >= p.Hkv) return;
+  if (rows_here > ROWS_WG || first_slot < 0 || wf >= wl || head >= p.Hkv) return;
+  if (trow >= rows_here) return;
   const int T_row = rt * ROWS_WG + trow;
   const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
   if (row0 + nn >= p.total_rows) return;
@@ -752,15 +753,21 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
     return sc_.part_ml + (slot * ROWS_WG + trow) * 2;
   };
-  auto acc_of = [&](int pi) -> const f32x2* {
+  auto acc_of = [&](int pi) -> const f32x4* {
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
-    return reinterpret_cast<const f32x2*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + lane;
+    return reinterpret_cast<const f32x4*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + l32;
   };
-  f32x2 num = {0.f, 0.f};
+  f32x4 num = {0.f, 0.f, 0.f, 0.f};
   float den = 0.f, M = -INFINITY;
+  auto add_piece = [&](float mc, float lc, const f32x4& a) {
+    const float wgt = mc == -INFINITY ? 0.f : exp2f(mc - M);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) num[e] = fmaf(wgt, a[e], num[e]);
+    den = fmaf(wgt, lc, den);
+  };
   if (np <= 4) {
     // the usual case: everything is requested at once, one memory latency
-    float mc[4], lc[4]; f32x2 a[4];
+    float mc[4], lc[4]; f32x4 a[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int pu = min(u, np - 1);
@@ -770,43 +777,37 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
 #pragma unroll
     for (int u = 0; u < 4; ++u) M = fmaxf(M, mc[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float wgt = mc[u] == -INFINITY ? 0.f : exp2f(mc[u] - M);
-      num[0] = fmaf(wgt, a[u][0], num[0]); num[1] = fmaf(wgt, a[u][1], num[1]);
-      den = fmaf(wgt, lc[u], den);
-    }
+    for (int u = 0; u < 4; ++u) add_piece(mc[u], lc[u], a[u]);
   } else {
-    // many pieces (a long item spread over many work-groups): maxima one piece per lane, then
-    // the partials four at a time
-    for (int p0 = 0; p0 < np; p0 += 64)
-      if (p0 + lane < np) M = fmaxf(M, ml_of(p0 + lane)[0]);
+    // many pieces (a long item spread over many work-groups): eight at a time, all of a batch
+    // requested together, with a running maximum (the sums are rescaled when it grows)
+    for (int p0 = 0; p0 < np; p0 += 8) {
+      float mc[8], lc[8]; f32x4 a[8];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-    int pi = 0;
-    for (; pi + 4 <= np; pi += 4) {
-      float mc[4], lc[4]; f32x2 a[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) { const float* ml = ml_of(pi + u); mc[u] = ml[0]; lc[u] = ml[1]; a[u] = *acc_of(pi + u); }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float wgt = mc[u] == -INFINITY ? 0.f : exp2f(mc[u] - M);
-        num[0] = fmaf(wgt, a[u][0], num[0]); num[1] = fmaf(wgt, a[u][1], num[1]);
-        den = fmaf(wgt, lc[u], den);
+      for (int u = 0; u < 8; ++u) {
+        const int pu = min(p0 + u, np - 1);
+        const float* ml = ml_of(pu);
+        mc[u] = p0 + u < np ? ml[0] : -INFINITY; lc[u] = ml[1]; a[u] = *acc_of(pu);
       }
-    }
-    for (; pi < np; ++pi) {
-      const float* ml = ml_of(pi);
-      const float mc = ml[0], lc = ml[1];
-      const f32x2 a = *acc_of(pi);
-      const float wgt = mc == -INFINITY ? 0.f : exp2f(mc - M);
-      num[0] = fmaf(wgt, a[0], num[0]); num[1] = fmaf(wgt, a[1], num[1]);
-      den = fmaf(wgt, lc, den);
+      float Mb = M;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) Mb = fmaxf(Mb, mc[u]);
+      if (Mb > M) {
+        const float r = M == -INFINITY ? 0.f : exp2f(M - Mb);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) num[e] *= r;
+        den *= r;
+        M = Mb;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) add_piece(mc[u], lc[u], a[u]);
     }
   }
   const float inv = den > 0.f ? 1.0f / den : 0.f;
   const long long orow = (long long)(row0 + nn) * p.Hq + hq;
-  reinterpret_cast<unsigned*>(reinterpret_cast<bf16_t*>(p.out) + orow * MF_D)[lane] = pack_bf16x2(num[0] * inv, num[1] * inv);
-  if (p.lse && lane == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
+  u32x2 packed = {pack_bf16x2(num[0] * inv, num[1] * inv), pack_bf16x2(num[2] * inv, num[3] * inv)};
+  reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(p.out) + orow * MF_D)[l32] = packed;
+  if (p.lse && l32 == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -893,7 +894,7 @@ hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, 0, sc, rows_wg);
-  dim3 grid(sc.num_wgs, rows_wg / 4);
+  dim3 grid(sc.num_wgs, rows_wg / 8);
   if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
   else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
   return hipGetLastError();
