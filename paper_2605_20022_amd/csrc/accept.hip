@@ -114,50 +114,49 @@ __global__ __launch_bounds__(ACC_BLOCK) void argmax_partial_kernel(
 // Greedy, pass 2: one wave per sequence.  Merge the segment results of each verify row,
 // then count the leading rows whose arg-max equals the token fed at the next row.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(FD_WAVE) void accept_greedy_epilogue_kernel(
+constexpr int GE_GROUP = 16;                       // lanes that merge one row's segments
+constexpr int GE_ROWS = ACC_BLOCK / GE_GROUP;     // rows merged at a time
+
+__global__ __launch_bounds__(ACC_BLOCK) void accept_greedy_epilogue_kernel(
     const float* __restrict__ part_val, const int* __restrict__ part_idx, int nseg,
     const int* __restrict__ row_indptr, const int* __restrict__ input_tokens,
     int total_rows, int max_rows_per_seq,
     int* __restrict__ accept_len, int* __restrict__ bonus_token, int* __restrict__ row_argmax) {
-  const int seq = blockIdx.x, lane = threadIdx.x;
+  const int seq = blockIdx.x, grp = threadIdx.x / GE_GROUP, gl = threadIdx.x % GE_GROUP;
   int r0 = clampi(row_indptr[seq], 0, total_rows);
   int k = clampi(row_indptr[seq + 1] - r0, 0, min(max_rows_per_seq, total_rows - r0));
-  if (k == 0) { if (lane == 0) { accept_len[seq] = 0; bonus_token[seq] = -1; } return; }
-  // first mismatching row (k-1 if none); rows handled 64 at a time, in order
-  int first_bad = k - 1, bonus = -1;
+  if (k == 0) { if (threadIdx.x == 0) { accept_len[seq] = 0; bonus_token[seq] = -1; } return; }
+  // Rows GE_ROWS at a time, in order: GE_GROUP lanes merge a row's segments (every load of a batch is
+  // in flight together); the first row whose arg-max differs from the token fed at the next row --
+  // or the last row -- ends the step and its arg-max is the bonus token.
+  __shared__ int s_first_bad, s_bonus;
+  if (threadIdx.x == 0) { s_first_bad = 0x7fffffff; s_bonus = -1; }
+  __syncthreads();
   bool done = false;
-  for (int base = 0; base < k && !done; base += FD_WAVE) {
-    int j = base + lane;
-    int a = -1; bool bad = false;
-    if (j < k) {
-      float bv = -INFINITY; int bi = 0x7fffffff;
-      for (int s = 0; s < nseg; ++s)
+  for (int j0 = 0; j0 < k; j0 += GE_ROWS) {
+    const int j = j0 + grp;
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    if (j < k)
+      for (int s = gl; s < nseg; s += GE_GROUP)
         amax_merge(bv, bi, part_val[(long long)(r0 + j) * nseg + s], part_idx[(long long)(r0 + j) * nseg + s]);
-      a = bi;
-      if (row_argmax) row_argmax[r0 + j] = a;
-      bad = (j == k - 1) || (a != input_tokens[r0 + j + 1]);
+#pragma unroll
+    for (int off = GE_GROUP / 2; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(bv, off); const int oi = __shfl_xor(bi, off);
+      amax_merge(bv, bi, ov, oi);
     }
-    unsigned long long m = __ballot(bad);
-    if (m && !done) {
-      int src = __ffsll((long long)m) - 1;
-      first_bad = base + src;
-      bonus = __shfl(a, src);
+    if (gl == 0 && j < k) {
+      if (row_argmax) row_argmax[r0 + j] = bi;
+      if (!done && ((j == k - 1) || (bi != input_tokens[r0 + j + 1]))) atomicMin(&s_first_bad, j);
+    }
+    __syncthreads();
+    if (!done && s_first_bad < j0 + GE_ROWS) {       // decided in this batch: its owner publishes the bonus token
+      if (gl == 0 && j == s_first_bad) s_bonus = bi;
       done = true;
-      // keep filling row_argmax for the remaining rows if it was requested
-      if (row_argmax) {
-        for (int b2 = base + FD_WAVE; b2 < k; b2 += FD_WAVE) {
-          int j2 = b2 + lane;
-          if (j2 < k) {
-            float bv = -INFINITY; int bi = 0x7fffffff;
-            for (int s = 0; s < nseg; ++s)
-              amax_merge(bv, bi, part_val[(long long)(r0 + j2) * nseg + s], part_idx[(long long)(r0 + j2) * nseg + s]);
-            row_argmax[r0 + j2] = bi;
-          }
-        }
-      }
+      if (!row_argmax) break;                        // (uniform) nothing else is wanted from the later rows
     }
   }
-  if (lane == 0) { accept_len[seq] = first_bad; bonus_token[seq] = bonus; }
+  __syncthreads();
+  if (threadIdx.x == 0) { accept_len[seq] = s_first_bad; bonus_token[seq] = s_bonus; }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -690,7 +689,7 @@ static hipError_t launch_greedy(const T* logits, long long row_stride, int vocab
     hipLaunchKernelGGL(argmax_partial_kernel<T>, dim3(nseg, total_rows), dim3(ACC_BLOCK), 0, st,
                        logits, row_stride, vocab, sl, pv, pi);
   if (batch > 0)
-    hipLaunchKernelGGL(accept_greedy_epilogue_kernel, dim3(batch), dim3(FD_WAVE), 0, st,
+    hipLaunchKernelGGL(accept_greedy_epilogue_kernel, dim3(batch), dim3(ACC_BLOCK), 0, st,
                        pv, pi, nseg, row_indptr, toks, total_rows, max_rows, accept_len, bonus, row_argmax);
   return hipGetLastError();
 }
