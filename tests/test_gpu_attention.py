@@ -122,6 +122,31 @@ def test_several_mask_blocks(fd, case):
     assert not np.array_equal(base[blk], moved[blk])
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_workloads(fd, seed):
+    """Seeded random shapes through the MFMA path: batch, head grouping, page size, ragged prefixes
+    (empty ones included), verify lengths (zero included), block length and count, share size."""
+    rng = np.random.default_rng(1000 + seed)
+    G = int(rng.choice([1, 2, 3, 4, 5, 8])); Hkv = int(rng.choice([1, 2, 3]))
+    B = int(rng.integers(1, 9)); ps = int(rng.choice([16, 32, 64]))
+    lo = int(rng.integers(0, 200)); hi = lo + int(rng.integers(0, 700))
+    klo = int(rng.integers(0, 4)); khi = klo + int(rng.integers(0, 10))
+    nb = int(rng.choice([1, 1, 2, 3])); mb = int(rng.integers(0 if khi > 0 and klo > 0 else 1, 12))
+    k_fixed = nb > 1                                        # several blocks: one verify length for all
+    w = W.AttnWorkload("rand", "bf16", B, G * Hkv, Hkv, 128, ps, (lo, hi),
+                       (max(khi, 1), max(khi, 1)) if k_fixed else (klo, khi), mb if nb == 1 else max(mb, 1), 1.0,
+                       seed=500 + seed, spare_page_frac=0.1, mask_blocks=nb)
+    inp = W.make_attention_inputs(w)
+    if inp["q"].shape[0] == 0:
+        pytest.skip("no new rows drawn")
+    chunk = int(rng.choice([0, 0, 64, 192, 512]))
+    what = f"random seed={seed}: B={B} G={G} Hkv={Hkv} ps={ps} kv=({lo},{hi}) k=({klo},{khi}) nb={nb} mb={mb} chunk={chunk}"
+    _check(fd, inp, "bf16", what, kv_chunk=chunk)
+    if nb == 1:
+        mv = np.array([rng.integers(0, k + 1) for k in inp["verify_len"]], dtype=np.int32)
+        _check(fd, inp, "bf16", what + " mask_vis", mask_vis=mv, kv_chunk=chunk)
+
+
 def test_par4_full_parallel_mode(fd):
     w, _ = W.CONFIGS["par4"]
     inp = W.make_attention_inputs(w)
