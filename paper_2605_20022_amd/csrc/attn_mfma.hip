@@ -19,7 +19,7 @@
 //                      registers: no per-lane address arithmetic, and rows past the end of the
 //                      prefix lie outside the descriptor and read as zero.  Two tiles are in
 //                      flight in registers while a third is multiplied.
-//   regs -> LDS        double buffered, K rows padded to 272 B, V rows to 288 B, one barrier/tile
+//   regs -> LDS        double buffered, K rows padded to 272 B, V rows to 320 B, one barrier/tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS (ds_read_b128),
 //                      B = Q fragments held in registers for the whole item
 //   online softmax     in the accumulator layout: a lane owns ONE query row (column of
@@ -54,8 +54,14 @@ namespace fd {
 constexpr int MF_BLOCK = 256;
 constexpr int MF_TK = 64;                 // keys per LDS tile
 constexpr int MF_D = 128;
-constexpr int MF_KSTR = MF_D + 8;         // K row pitch in bf16 elements (272 bytes)
-constexpr int MF_VSTR = MF_D + 16;        // V row pitch (288 bytes): best for the transpose reads
+#ifndef FD_KPAD
+#define FD_KPAD 8
+#endif
+#ifndef FD_VPAD
+#define FD_VPAD 32
+#endif
+constexpr int MF_KSTR = MF_D + FD_KPAD;   // K row pitch in bf16 elements (272 bytes)
+constexpr int MF_VSTR = MF_D + FD_VPAD;   // V row pitch (320 bytes): the transposing reads run without bank conflicts (counter-checked; 288 B costs 2 cycles per read)
 constexpr int MF_K_ELEMS = MF_TK * MF_KSTR;
 constexpr int MF_V_ELEMS = MF_TK * MF_VSTR;
 constexpr int MF_BUF_ELEMS = MF_K_ELEMS + MF_V_ELEMS;     // one K+V tile
