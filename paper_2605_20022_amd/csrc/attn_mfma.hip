@@ -68,6 +68,7 @@ constexpr int MF_BUF_ELEMS = MF_K_ELEMS + MF_V_ELEMS;     // one K+V tile
 constexpr size_t MF_LDS_BYTES = (size_t)2 * MF_BUF_ELEMS * sizeof(bf16_t);   // double buffered
 constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
 constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
+constexpr float MF_LAZY = 6.f;            // the softmax reference follows the row maximum in steps of at least 2^6
 constexpr int MF_START_COST = 2;          // what starting an item costs a work-group, in tile times
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -571,7 +572,12 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
           for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sc[i]);
           mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float m_new = fmaxf(m_run, mx * cs);
+          // The running reference m_run only follows the row maximum when that has moved up by more
+          // than MF_LAZY (base-2 units): probabilities are then at most 2^MF_LAZY instead of 1, which
+          // fp32 sums and bf16 P carry with the same relative precision, and the 64 accumulator
+          // multiplications below run for a few tiles per item instead of for most of them.
+          const float m_cand = fmaxf(m_run, mx * cs);
+          const float m_new = m_cand > m_run + MF_LAZY ? m_cand : m_run;     // (-inf + MF_LAZY = -inf: first visible key)
           const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;  // row with nothing visible yet
           const float alpha = __builtin_amdgcn_exp2f(m_run - m_sub);
           m_run = m_new;
