@@ -83,3 +83,33 @@ def test_accept_workspace_query_and_validation():
     assert rc == 1 and b"row_stride" in lib.fd_last_error()
     rc = lib.fd_accept_sample(None, None, fd.FD_BF16, 20, 20, 1.0, None, None, None, None, 0, 0, 0, None, None, None, 0, None)
     assert rc == 0      # empty batch: nothing to do
+
+
+def test_widened_entry_points_validate_on_the_host():
+    """fd_draft_select, fd_select_branch, fd_append_kv: workspace query and the argument errors that
+    are detected before anything is launched."""
+    lib = fd.load()
+    ws = fd.fd_draft_select_workspace(480, 151936)
+    assert ws > 0 and ws % 256 == 0 and fd.fd_draft_select_workspace(1, 0) == 0
+    f = lib.fd_draft_select
+    # temperature must be positive; the threshold finite; the row stride at least the vocabulary
+    assert f(None, fd.FD_BF16, 100, 100, 0.0, 0.3, None, 1, 1, 1, None, None, None, None, 0, None) == 1
+    assert b"temperature" in lib.fd_last_error()
+    assert f(None, fd.FD_BF16, 100, 100, 1.0, float("nan"), None, 1, 1, 1, None, None, None, None, 0, None) == 1
+    assert f(None, fd.FD_BF16, 50, 100, 1.0, 0.3, None, 1, 1, 1, None, None, None, None, 0, None) == 1
+    assert b"row_stride" in lib.fd_last_error()
+    assert f(None, fd.FD_BF16, 100, 100, 1.0, 0.3, None, 0, 0, 0, None, None, None, None, 0, None) == 0   # empty batch
+    assert f(None, fd.FD_BF16, 100, 100, 1.0, 0.3, None, 1, 1, 1, None, None, None, None, 0, None) == 1   # NULL pointers
+    # branch selection
+    assert lib.fd_select_branch(None, None, None, None, None, -1, 0, 0, None, None, None) == 1
+    assert lib.fd_select_branch(None, None, None, None, None, 0, 0, 0, None, None, None) == 0
+    assert lib.fd_select_branch(None, None, None, None, None, 2, 4, 2, None, None, None) == 1
+    # commit of accepted rows
+    assert lib.fd_append_kv(None, None, None, None) == 1
+    a = fd.fd_attn_args()
+    a.dtype = fd.FD_BF16; a.batch = 0; a.num_kv_heads = 8; a.head_dim = 128; a.page_size = 16
+    assert lib.fd_append_kv(C.byref(a), None, None, None) == 0                   # empty batch
+    a.batch = 2
+    assert lib.fd_append_kv(C.byref(a), None, None, None) == 1 and b"NULL" in lib.fd_last_error()
+    a.head_dim = 100
+    assert lib.fd_append_kv(C.byref(a), None, None, None) == 1
