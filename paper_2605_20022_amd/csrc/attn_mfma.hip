@@ -571,7 +571,13 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           float mx = fmaxf(sc[0], sc[1]);
 #pragma unroll
           for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sc[i]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          // the other half of the row's keys is held by lane ^ 32: one v_permlane32_swap gives both
+          // halves' maxima in every lane (no trip through LDS as a generic shuffle would make)
+          {
+            const unsigned mu = __builtin_bit_cast(unsigned, mx);
+            const auto sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
+            mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
+          }
           // The running reference m_run only follows the row maximum when that has moved up by more
           // than MF_LAZY (base-2 units): probabilities are then at most 2^MF_LAZY instead of 1, which
           // fp32 sums and bf16 P carry with the same relative precision, and the 64 accumulator
