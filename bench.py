@@ -285,6 +285,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run the library's plain 1 GiB streaming copy (bandwidth yard-stick, counter calibration)")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="only run the library's staged streaming read over buffers of cfg3's, cfg5's and cfg4's KV size")
     ap.add_argument("--draft-select", action="store_true",
                     help="only time fd_draft_select (selective verification) on 32 x 15 rows of vocab 151936")
     args = ap.parse_args()
@@ -317,6 +319,28 @@ def main():
         dt = (time.perf_counter() - t0) / args.steps
         print(json.dumps({"probe": "stream_copy", "bytes_read": n, "bytes_written": n, "launches": args.steps + 3,
                           "ms": round(dt * 1e3, 4), "GBps_read_plus_write": round(2 * n / dt / 1e9, 1)}), flush=True)
+        return
+
+    if args.read_probe:
+        from paper_2605_20022_amd import workloads as W
+        res = []
+        sums = torch.empty(fd.STREAM_READ_SUMS, dtype=torch.int32, device="cuda")
+        for name in ("cfg3", "cfg5", "cfg4"):
+            w = W.CONFIGS[name][0]
+            n = W.kv_bytes(w, W.make_lengths(w)["kv_len"]) // 32768 * 32768
+            pools = max(2, -(-(5 << 28) // n))                 # >= 1.25 GB of distinct data: every launch reads cold memory
+            bufs = [torch.ones(n // 4, dtype=torch.int32, device="cuda") for _ in range(pools)]
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for i in range(3):
+                fd.fd_stream_read(bufs[i % pools], sums)
+            for i, (e0, e1) in enumerate(ev):
+                e0.record(); fd.fd_stream_read(bufs[i % pools], sums); e1.record()
+            torch.cuda.synchronize()
+            us = np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in ev])
+            res.append({"bytes_of": name, "bytes": n, "launches": args.steps, "us_mean": round(float(us.mean()), 2),
+                        "us_min": round(float(us.min()), 2), "GBps": round(n / us.mean() / 1e3, 1)})
+            del bufs
+        print(json.dumps({"probe": "stream_read", "sizes": res}), flush=True)
         return
 
     st = Step(fd, args.workload, torch)

@@ -274,6 +274,14 @@ FD_API int32_t   fd_profile_end(float *ms_out, int32_t capacity);
  * yard-stick, and the known-size kernel the HBM traffic counters are scaled against. */
 FD_API fd_status fd_stream_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 
+/* Staged streaming read of `bytes` (device, multiple of 32768, 16-byte aligned), asynchronous on
+ * hip_stream: the attention kernel's launch shape and load scheme with no page table and no
+ * arithmetic (512 work-groups of 256 threads, 32 KB tiles staged in registers, passed through LDS
+ * and read back once).  sums (device, 512 * 256 words, caller-owned) receives one 32-bit word sum
+ * per thread; their total is the sum of all 32-bit words of the buffer modulo 2^32.  It exists for
+ * measurement: the best a job of a given size can reach with this scheme. */
+FD_API fd_status fd_stream_read(const void *src, size_t bytes, uint32_t *sums, void *hip_stream);
+
 /* Library version string, e.g. "flexdraft-gfx950 0.1". */
 FD_API const char *fd_version(void);
 

@@ -34,6 +34,7 @@ hipError_t run_accept_sample(const void* target, const void* draft, int dt, long
                              const float* ur, int batch, int total_rows, int max_rows, int* accept_len,
                              int* bonus, void* ws, hipStream_t st);
 hipError_t run_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+hipError_t run_stream_read(const void* src, size_t bytes, unsigned* sums, hipStream_t st);
 }  // namespace fd
 
 namespace {
@@ -407,6 +408,15 @@ fd_status fd_stream_copy(const void* src, void* dst, size_t bytes, void* hip_str
   if (bytes == 0) return FD_OK;
   hipError_t e = fd::run_stream_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(FD_ERR_HIP, "copy launch: %s", hipGetErrorString(e));
+  return FD_OK;
+}
+
+fd_status fd_stream_read(const void* src, size_t bytes, uint32_t* sums, void* hip_stream) {
+  if (!src || !sums) return fail(FD_ERR_INVALID_ARG, "src / sums NULL");
+  if (bytes % 32768 || !aligned16(src)) return fail(FD_ERR_INVALID_ARG, "read probe: bytes must be a multiple of 32768 and src 16-byte aligned");
+  g_err[0] = 0;
+  hipError_t e = fd::run_stream_read(src, bytes, sums, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(FD_ERR_HIP, "read probe launch: %s", hipGetErrorString(e));
   return FD_OK;
 }
 

@@ -50,7 +50,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy",
+           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy", "fd_stream_read",
            "fd_version"]
 
 
@@ -95,6 +95,8 @@ def load() -> C.CDLL:
     lib.fd_profile_end.argtypes = [C.POINTER(C.c_float), C.c_int32]
     lib.fd_stream_copy.restype = C.c_int
     lib.fd_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fd_stream_read.restype = C.c_int
+    lib.fd_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.fd_version.restype = C.c_char_p
     _lib = lib
     return lib
@@ -259,6 +261,17 @@ def fd_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, out_to
 def fd_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     _check(load().fd_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+
+STREAM_READ_SUMS = 512 * 256
+
+
+def fd_stream_read(src: torch.Tensor, sums: torch.Tensor, stream=None) -> None:
+    """Staged read of `src` (bytes a multiple of 32768); sums: int32/uint32 device tensor of 512 * 256 words."""
+    nbytes = src.numel() * src.element_size()
+    if sums.numel() != STREAM_READ_SUMS or sums.element_size() != 4 or not sums.is_contiguous():
+        raise ValueError("sums must be a contiguous tensor of 512 * 256 32-bit words")
+    _check(load().fd_stream_read(_ptr(src), nbytes, _ptr(sums), _stream(stream)))
 
 
 def fd_version() -> str:

@@ -113,3 +113,11 @@ def test_widened_entry_points_validate_on_the_host():
     assert lib.fd_append_kv(C.byref(a), None, None, None) == 1 and b"NULL" in lib.fd_last_error()
     a.head_dim = 100
     assert lib.fd_append_kv(C.byref(a), None, None, None) == 1
+
+
+def test_measurement_probes_validate_on_the_host():
+    """fd_stream_copy / fd_stream_read reject NULL pointers and sizes that are not whole units."""
+    lib = fd.load()
+    assert lib.fd_stream_copy(None, None, 16, None) == 1
+    assert lib.fd_stream_read(None, 32768, None, None) == 1 and b"NULL" in lib.fd_last_error()
+    assert lib.fd_stream_read(C.c_void_p(4096), 1000, C.c_void_p(4096), None) == 1 and b"32768" in lib.fd_last_error()
