@@ -100,7 +100,7 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
     return fail(FD_ERR_UNSUPPORTED, "max_new_rows * heads too large for one launch");
   if (plan->use_mfma) {
     // the persistent kernel counts (sequence, head, row block, 64-key tile) units in 32 bits
-    const long long tiles = (long long)(a->max_kv_len + tile_keys - 1) / tile_keys + (a->max_new_rows + tile_keys - 1) / tile_keys + 2;   // + start-up units
+    const long long tiles = (long long)(a->max_kv_len + tile_keys - 1) / tile_keys + (a->max_new_rows + tile_keys - 1) / tile_keys + 4;   // + start-up units
     const double units = (double)(a->batch > 0 ? a->batch : 1) * a->num_kv_heads * plan->row_tiles * (double)tiles;
     if (units >= 2147483648.0) return fail(FD_ERR_UNSUPPORTED, "batch x heads x rows x kv length too large for one launch");
   }

@@ -69,7 +69,10 @@ constexpr size_t MF_LDS_BYTES = (size_t)2 * MF_BUF_ELEMS * sizeof(bf16_t);   // 
 constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
 constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
 constexpr float MF_LAZY = 6.f;            // the softmax reference follows the row maximum in steps of at least 2^6
-constexpr int MF_START_COST = 2;          // what starting an item costs a work-group, in tile times
+// What starting an item costs a work-group, in tile times: measured ≈ 6.9 µs (request the next piece's
+// tiles ≈ 2.4, merge and store ≈ 3.4, wait for the first tile ≈ 1.1) against 2.1 µs per tile in the
+// 64-row variant, about half as many of the longer tiles of the 128-row variant.
+constexpr int mf_start_cost(int maxrb) { return maxrb == 4 ? 2 : 4; }
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -108,9 +111,9 @@ __device__ __forceinline__ void seq_shape(const AttnParams& p, const SeqInfo& s,
 // Work units of one item with `tiles` tiles.  The line of work is cut into shares of equal
 // *time*, not of equal tile count: beginning an item (new query rows, new page list, the merge
 // and the stores of the one before) costs about as much as streaming two tiles, so every item is
-// preceded by MF_START_COST units that stand for no tile.  A work-group whose share holds an
+// preceded by `start_cost` units that stand for no tile.  A work-group whose share holds an
 // item boundary gets that many tiles less.
-__device__ __forceinline__ int item_units(int tiles) { return tiles > 0 ? tiles + MF_START_COST : 0; }
+__device__ __forceinline__ int item_units(int tiles, int start_cost) { return tiles > 0 ? tiles + start_cost : 0; }
 
 // A 64-bit value known to be equal in every lane, moved to scalar registers.
 __device__ __forceinline__ long long uniform_ll(long long v) {
@@ -131,6 +134,7 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 template <int DBG, int MAXRB>
 __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int MF_START_COST = mf_start_cost(MAXRB);
   constexpr int PF_K = FD_PF_K, PF_V = FD_PF_V;   // LDS fragment requests run this many MFMAs ahead
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   __shared__ int sh_w[MF_BLOCK / 64];
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (tid < p.B) {
       s_mine = load_seq_t<false>(p, tid, &bad);
       int T_, I_; seq_shape(p, s_mine, ROWS_WG, T_, I_);
-      vt = item_units(T_) * I_;
+      vt = item_units(T_, MF_START_COST) * I_;
     }
     const int it = wave_incl_scan(vt, lane);
     if (lane == 63) sh_w[wave] = it;
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     for (int i = tid; i < p.B; i += MF_BLOCK) {
       SeqInfo s = load_seq_t<false>(p, i);
       int T_, I_; seq_shape(p, s, ROWS_WG, T_, I_);
-      part += item_units(T_) * I_;
+      part += item_units(T_, MF_START_COST) * I_;
     }
     part = wave_incl_scan(part, lane);
     if (lane == 63) sh_w[wave] = part;
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       const int i = blk + tid;
       int T_ = 0, I_ = 0;
       if (i < p.B) { SeqInfo s = load_seq_t<false>(p, i); seq_shape(p, s, ROWS_WG, T_, I_); }
-      const int vt = item_units(T_) * I_;
+      const int vt = item_units(T_, MF_START_COST) * I_;
       const int it = wave_incl_scan(vt, lane);
       if (lane == 63) sh_w[wave] = it;
       __syncthreads();
@@ -295,14 +299,14 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // descriptor of the piece that starts at unit g of the line (g < g1); false if the data ran out.
   // A piece may hold no tile at all (its units are start-up units only): pc.nt == 0.
   auto make_piece = [&](unsigned g, Piece& pc) -> bool {
-    while (g >= Pt + (unsigned)(item_units(T) * I)) {
-      Pt += (unsigned)(item_units(T) * I);
+    while (g >= Pt + (unsigned)(item_units(T, MF_START_COST) * I)) {
+      Pt += (unsigned)(item_units(T, MF_START_COST) * I);
       ++seq;
       if (seq >= p.B) return false;
       ws = get_seq(seq);
       seq_shape(p, ws, ROWS_WG, T, I);
     }
-    const int Tu = item_units(T);
+    const int Tu = item_units(T, MF_START_COST);
     const int local = (int)(g - Pt);
     const int item = local / Tu;
     const int u = local - item * Tu;                               // unit within the item
