@@ -120,9 +120,10 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
     l_run = l_run * alpha + psum;
     m_run = m_new;
     __syncthreads();
-    // output columns sub, sub+16, ...
+    // output columns sub, sub+16, ... (D is a multiple of 8, not necessarily of 16)
     for (int j = 0; j * 16 < D; ++j) {
       int d = sub + 16 * j;
+      if (d >= D) break;
       float a = acc[j] * alpha;
       for (int kk = 0; kk < GEN_KEYS; ++kk) a = fmaf(Ps[my_row][kk], Vs[kk][d], a);
       acc[j] = a;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(GEN_BLOCK) void attn_generic_kernel(AttnParams p) {
   if (my_T < rows_total) {
     int hq = g * p.G + my_T % p.G;
     long long slot = ((long long)chunk_id * p.total_rows + (s.row0 + my_nn)) * p.Hq + hq;
-    for (int j = 0; j * 16 < D; ++j) p.part_acc[slot * D + sub + 16 * j] = acc[j];
+    for (int j = 0; sub + 16 * j < D; ++j) p.part_acc[slot * D + sub + 16 * j] = acc[j];
     if (sub == 0) { p.part_ml[slot * 2] = m_run; p.part_ml[slot * 2 + 1] = l_run; }
   }
 }

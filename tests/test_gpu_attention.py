@@ -46,6 +46,8 @@ def test_cfg1_tiny_fp32(fd):
     dict(B=2, Hq=8, Hkv=1, D=128, ps=8, kv=(30, 90), kr=(0, 3), m=4),       # k may be 0: mask-only rows
     dict(B=4, Hq=6, Hkv=3, D=32, ps=1, kv=(0, 40), kr=(1, 4), m=0),         # page size 1, empty prefixes
     dict(B=2, Hq=2, Hkv=2, D=128, ps=32, kv=(100, 300), kr=(2, 20), m=9),   # > 16 tile rows: several row tiles
+    dict(B=4, Hq=8, Hkv=2, D=8, ps=4, kv=(90, 110), kr=(1, 1), m=15),       # head_dim 8: half of a 16-column group
+    dict(B=2, Hq=4, Hkv=1, D=40, ps=16, kv=(10, 150), kr=(1, 4), m=3),      # head_dim a multiple of 8, not of 16
 ])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_generic_kernel_small_cases(fd, case, dtype):
