@@ -137,6 +137,31 @@ def test_cfg5_sampling_vocab_151936(fd):
     assert o_acc.min() >= 0 and o_acc.max() <= 15
 
 
+@pytest.mark.parametrize("B,V,dtype", [(4, 1048576, "bf16"), (65535, 5, "f32"), (6000, 97, "bf16")])
+def test_acceptance_extreme_shapes(fd, B, V, dtype):
+    """A vocabulary of 2^20 entries, the largest row count the entry points take (65535), thousands of
+    ragged sequences: greedy, sampling and draft selection against the oracle."""
+    rng = np.random.default_rng(B + V)
+    ks = np.ones(B, dtype=np.int64) if B == 65535 else rng.integers(0, 12, size=B)
+    if B == 4:
+        ks = np.array([3, 0, 1, 5])
+    indptr = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+    Rv = int(indptr[-1])
+    vals = (rng.standard_normal((Rv, V)) * 3).astype(np.float32)
+    vals[Rv // 2, V - 1] = 50.0                          # a maximum in the very last slot
+    logits = W.f32_to_bf16_bits(vals) if dtype == "bf16" else vals
+    _, _, am = oc.accept_greedy(logits, indptr, np.zeros(Rv, dtype=np.int64))
+    toks = rng.integers(0, V, size=Rv)
+    agree = rng.random(Rv) < 0.8
+    toks[1:][agree[:-1]] = am[:-1][agree[:-1]]
+    _greedy_case(fd, logits, indptr, toks.astype(np.int32))
+    a = W.AcceptWorkload("s", dtype, V, "sample", 2.0, draft_noise_std=0.7, temperature=0.8, seed=B)
+    _, thin = _sample_case(fd, a, indptr, 0.8)
+    assert thin <= max(1, Rv // 2000)
+    lg = W.make_peaked_logits(V, Rv, seed=B, dtype=dtype, peak_lo=2.0, peak_hi=12.0)
+    _draft_select_case(fd, lg, indptr, 1.0, 0.3)
+
+
 def test_acceptance_argument_errors(fd):
     import torch
     lg = torch.zeros((2, 64), dtype=torch.float32, device="cuda")

@@ -149,6 +149,16 @@ def test_random_workloads(fd, seed):
         _check(fd, inp, "bf16", what + " mask_vis", mask_vis=mv, kv_chunk=chunk)
 
 
+@pytest.mark.parametrize("B,kv,dtype,flags", [(5000, (0, 40), "bf16", 0), (5000, (0, 40), "bf16", FORCE_GENERIC),
+                                              (20000, (0, 3), "bf16", 0), (3000, (0, 70), "f32", 0)])
+def test_thousands_of_sequences(fd, B, kv, dtype, flags):
+    """Batches far beyond one work-group's scan block, most prefixes shorter than a tile, some empty."""
+    w = W.AttnWorkload("many", dtype, B, 8, 2, 128, 16, kv, (0, 2), 1, 1.0, seed=40 + B, spare_page_frac=0.05)
+    inp = W.make_attention_inputs(w)
+    for chunk in (0, 64):
+        _check(fd, inp, dtype, f"many B={B} kv={kv} {dtype} flags={flags} chunk={chunk}", kv_chunk=chunk, flags=flags)
+
+
 def test_par4_full_parallel_mode(fd):
     w, _ = W.CONFIGS["par4"]
     inp = W.make_attention_inputs(w)
