@@ -22,10 +22,11 @@
  *     detected on the host before anything is launched.  fd_last_error() returns
  *     a thread-local description of the last failure.
  *   - Device-side data that contradicts the host-side bounds (a kv_len above
- *     max_kv_len, a page id outside [0, num_pages), a token id outside the
- *     vocabulary, ...) is clamped by the kernels so that no access leaves the
- *     caller's buffers, and the matching bit is OR-ed into *status if a status
- *     word was supplied.  The numerical result of such a call is unspecified.
+ *     max_kv_len, a page id outside [0, num_pages), a page_indptr entry above
+ *     page_indices_len, a token id outside the vocabulary, ...) is clamped by the
+ *     kernels so that no access leaves the caller's buffers, and the matching bit
+ *     is OR-ed into *status if a status word was supplied.  The numerical result
+ *     of such a call is unspecified.
  *
  * Row convention (shared by all three calls)
  *   Sequence i feeds n_i = k_i + m_i new rows into the pass: first k_i verify
@@ -115,7 +116,9 @@ typedef struct fd_attn_args {
   int32_t kv_chunk;           /* 0 => automatic.  > 0 (multiple of 64): keys of work handed to
                                * one work-group - the chunk of a sequence's prefix (fp32
                                * kernel) or the share of the batch's key tiles (MFMA kernel) */
-  int32_t reserved;
+  int32_t page_indices_len;   /* entries in page_indices; page_indptr is checked against it.
+                               * 0 => not given: page_indptr is then trusted (the one device
+                               * array whose extent the kernels cannot otherwise know)       */
   const void *k_cache;        /* device                                                       */
   const void *v_cache;        /* device                                                       */
   int64_t cache_stride_page, cache_stride_head, cache_stride_token;

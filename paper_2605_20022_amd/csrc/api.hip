@@ -85,6 +85,7 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
   if (a->dtype != FD_F32 && a->dtype != FD_BF16) return fail(FD_ERR_INVALID_ARG, "unknown dtype %d", a->dtype);
   if (!(a->sm_scale >= 0.f) || isinf(a->sm_scale)) return fail(FD_ERR_INVALID_ARG, "sm_scale must be finite and >= 0");
   if (a->kv_chunk < 0 || a->kv_chunk % 64) return fail(FD_ERR_INVALID_ARG, "kv_chunk %d must be a non-negative multiple of 64", a->kv_chunk);
+  if (a->page_indices_len < 0) return fail(FD_ERR_INVALID_ARG, "page_indices_len %d is negative", a->page_indices_len);
   if (a->batch > 65535) return fail(FD_ERR_UNSUPPORTED, "batch %d > 65535", a->batch);
   if (a->max_kv_len > (1 << 30)) return fail(FD_ERR_UNSUPPORTED, "max_kv_len %d too large", a->max_kv_len);
 
@@ -180,7 +181,7 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   p.B = a->batch; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads; p.D = a->head_dim;
   p.G = p.Hq / p.Hkv; p.page_size = a->page_size;
   p.total_rows = a->total_rows; p.max_kv_len = a->max_kv_len; p.max_new_rows = a->max_new_rows;
-  p.num_pages = a->num_pages; p.chunk = plan.chunk; p.max_chunks = plan.max_chunks; p.row_tiles = plan.row_tiles;
+  p.num_pages = a->num_pages; p.page_entries = a->page_indices_len; p.chunk = plan.chunk; p.max_chunks = plan.max_chunks; p.row_tiles = plan.row_tiles;
   p.sm_scale = a->sm_scale > 0.f ? a->sm_scale : 1.0f / sqrtf((float)a->head_dim);
   p.k_cache = a->k_cache; p.v_cache = a->v_cache;
   p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
@@ -373,7 +374,7 @@ fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t
   p.G = a->num_kv_heads > 0 && a->num_q_heads > 0 ? a->num_q_heads / a->num_kv_heads : 1;
   p.page_size = a->page_size;
   p.total_rows = a->total_rows; p.max_kv_len = a->max_kv_len; p.max_new_rows = a->max_new_rows;
-  p.num_pages = a->num_pages;
+  p.num_pages = a->num_pages; p.page_entries = a->page_indices_len < 0 ? 0 : a->page_indices_len;
   p.k_cache = a->k_cache; p.v_cache = a->v_cache;
   p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
   p.page_indptr = a->page_indptr; p.page_indices = a->page_indices; p.kv_len = a->kv_len;

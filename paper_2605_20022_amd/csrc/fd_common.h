@@ -65,6 +65,7 @@ struct SeqInfo {
 struct AttnParams {
   int B, Hq, Hkv, D, G, page_size;
   int total_rows, max_kv_len, max_new_rows, num_pages;
+  int page_entries;   // length of page_indices, 0 = unknown (page_indptr is then trusted)
   int chunk;          // cached tokens per work-group
   int max_chunks;     // grid extent over chunks
   int row_tiles;      // grid extent over row tiles
@@ -117,10 +118,16 @@ __device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i, uint32
     v = clampi(v, 0, s.k);
   }
   s.v = v;
+  bool list_bad = pg0 < 0;
+  if (p.page_entries > 0 && (pg0 > p.page_entries || pg1 > p.page_entries)) {      // list runs past the array
+    list_bad = true;
+    pg0 = pg0 > p.page_entries ? p.page_entries : pg0;
+    pg1 = pg1 > p.page_entries ? p.page_entries : pg1;
+  }
   s.page0 = pg0 < 0 ? 0 : pg0;
-  s.npages = pg1 - pg0 < 0 ? 0 : pg1 - pg0;
+  s.npages = pg1 - s.page0 < 0 ? 0 : pg1 - s.page0;
   int need = (s.L + p.page_size - 1) / p.page_size;
-  if (pg0 < 0 || need > s.npages) {       // page list shorter than kv_len claims
+  if (list_bad || need > s.npages) {      // page list shorter than kv_len claims
     bad |= FD_DEV_PAGE_RANGE;
     s.L = s.npages * p.page_size < s.L ? s.npages * p.page_size : s.L;
   }

@@ -28,7 +28,7 @@ class fd_attn_args(C.Structure):
         ("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("page_size", C.c_int32), ("dtype", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_int32),
         ("total_rows", C.c_int32), ("max_kv_len", C.c_int32), ("max_new_rows", C.c_int32), ("num_pages", C.c_int32),
-        ("kv_chunk", C.c_int32), ("reserved", C.c_int32),
+        ("kv_chunk", C.c_int32), ("page_indices_len", C.c_int32),
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("cache_stride_page", C.c_int64), ("cache_stride_head", C.c_int64), ("cache_stride_token", C.c_int64),
         ("page_indptr", C.c_void_p), ("page_indices", C.c_void_p), ("kv_len", C.c_void_p),
@@ -147,7 +147,7 @@ def make_attn_args(q, k_new, v_new, k_cache, v_cache, page_indptr, page_indices,
     a.batch = kv_len.shape[0]; a.num_q_heads = Hq; a.num_kv_heads = Hkv; a.head_dim = D
     a.page_size = k_cache.shape[2]; a.dtype = _dtype_code(q); a.sm_scale = sm_scale; a.flags = flags
     a.total_rows = R; a.max_kv_len = int(max_kv_len); a.max_new_rows = int(max_new_rows)
-    a.num_pages = k_cache.shape[0]; a.kv_chunk = kv_chunk; a.reserved = 0
+    a.num_pages = k_cache.shape[0]; a.kv_chunk = kv_chunk; a.page_indices_len = page_indices.numel()
     a.k_cache = k_cache.data_ptr(); a.v_cache = v_cache.data_ptr()
     a.cache_stride_page = k_cache.stride(0); a.cache_stride_head = k_cache.stride(1)
     a.cache_stride_token = k_cache.stride(2)

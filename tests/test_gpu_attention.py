@@ -291,6 +291,15 @@ def test_argument_errors_and_device_status(fd):
     fd.fd_verify_draft_attn(call2.args)
     torch.cuda.synchronize()
     assert int(call2.status.item()) & 4
+    # a page list that runs past the end of page_indices is cut at the array's length (given in
+    # page_indices_len) and reported, by both kernels
+    for flags in (0, FORCE_GENERIC):
+        call3 = AttnCall(fd, inp, flags=flags)
+        assert call3.args.page_indices_len == call3.d["page_indices"].numel()
+        call3.d["page_indptr"][1] = 10 ** 6
+        fd.fd_verify_draft_attn(call3.args)
+        torch.cuda.synchronize()
+        assert int(call3.status.item()) & 4
     # empty batch is a no-op
     empty = AttnCall(fd, subset_inputs(inp, []))
     fd.fd_verify_draft_attn(empty.args)

@@ -73,6 +73,11 @@ def test_attention_workspace_query_and_validation():
     assert e.value.code == 1 and "NULL" in str(e.value)
 
 
+def test_negative_page_list_length_is_rejected():
+    assert fd.fd_verify_draft_attn_workspace(_args(page_indices_len=-1)) == 0
+    assert fd.fd_verify_draft_attn_workspace(_args(page_indices_len=0)) > 0
+
+
 def test_accept_workspace_query_and_validation():
     g = fd.fd_accept_workspace(16, 128, 151936, False)
     s = fd.fd_accept_workspace(4, 64, 151936, True)
