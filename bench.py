@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 COLD_FOOTPRINT = 1.25e9         # bytes of distinct copies a rotating input must span
+PROFILE_STRIDE = 8               # every how many steps of the timed region the streaming kernel is event-bracketed
 
 
 def log(*a):
@@ -139,13 +140,14 @@ class Step:
         rows = int((acc + 1).sum().item())
         return {"append_us": round(ts[len(ts) // 2] * 1e3, 2), "append_rows": rows}
 
-    def timed(self, steps, warmup, profile_kernel=False):
+    def timed(self, steps, warmup, profile_kernel=False, stride=PROFILE_STRIDE):
         torch = self.torch
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
         if profile_kernel:
-            self.fd.fd_profile_begin(steps)
+            # an event pair costs the stream about 5 us: bracket every 8th launch of the timed region
+            self.fd.fd_profile_begin((steps + stride - 1) // stride, stride)
         t0 = time.perf_counter()
         for _ in range(steps):
             self.step()
@@ -366,6 +368,7 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4) if achieved else None,
                      "traffic": read_traffic(args.workload), "kernel": "attn_mfma_kernel",
                      "kernel_avg_ms": round(kern_avg_ms, 5) if kern_avg_ms else None,
+                     "kernel_launches_timed": len(kern_ms), "event_stride": PROFILE_STRIDE,
                      "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2) if kern_avg_ms else None},
     }
     if "accept" in parts:
@@ -379,7 +382,7 @@ def main():
         for name in ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4", "q3_1p7b", "q3_14b", "q3_32b"]:
             s2 = Step(fd, name, torch)
             n = 50
-            _, km = s2.timed(n, 5, profile_kernel=True)
+            _, km = s2.timed(n, 5, profile_kernel=True, stride=1)
             p2 = s2.timed_parts(n, 3)
             k_ms = float(np.mean(km))
             per[name] = {"kv_MB": round(s2.kv_bytes / 1e6, 2), "kernel_us": round(k_ms * 1e3, 2),

@@ -262,14 +262,15 @@ FD_API fd_status fd_select_branch(const int32_t *block_tokens, const int32_t *bl
 FD_API const char *fd_last_error(void);
 
 /*
- * Kernel timing for benchmarks.  fd_profile_begin(n) creates 2n HIP events; while
- * profiling is on, each fd_verify_draft_attn call records one (start, stop) pair
- * around its main streaming kernel on the call's stream (calls beyond n are not
- * recorded).  fd_profile_end synchronises the recorded events, writes up to
+ * Kernel timing for benchmarks.  fd_profile_begin(n, stride) creates 2n HIP events; while
+ * profiling is on, every stride-th fd_verify_draft_attn call (the first one included)
+ * records one (start, stop) pair around its main streaming kernel on the call's stream,
+ * until n pairs are recorded.  An event costs the stream a few microseconds, so a stride
+ * above 1 keeps a timed loop close to its undisturbed pace.  fd_profile_end synchronises the recorded events, writes up to
  * `capacity` durations in milliseconds to ms_out (host), destroys the events and
  * returns the number written.  Not thread-safe; off by default.
  */
-FD_API fd_status fd_profile_begin(int32_t max_calls);
+FD_API fd_status fd_profile_begin(int32_t max_calls, int32_t stride);
 FD_API int32_t   fd_profile_end(float *ms_out, int32_t capacity);
 
 /* Plain device-to-device streaming copy of `bytes` (multiple of 16, both pointers 16-byte

@@ -52,7 +52,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 
 // profiling state (fd_profile_begin / fd_profile_end)
 hipEvent_t* g_prof_events = nullptr;
-int g_prof_cap = 0, g_prof_used = 0;
+int g_prof_cap = 0, g_prof_used = 0, g_prof_stride = 1, g_prof_seen = 0;
 
 // Builds with -DFD_MEASURE carry two timing-only variants of the MFMA kernel (selected by bits
 // 8-9 of flags; their output is meaningless); the product build has neither.
@@ -197,7 +197,7 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
 #endif
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  const bool prof = g_prof_events && g_prof_used < g_prof_cap;
+  const bool prof = g_prof_events && g_prof_used < g_prof_cap && (g_prof_seen++ % g_prof_stride) == 0;
   if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
     return fail(FD_ERR_HIP, "hipEventRecord failed");
   hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, measure_variant(a->flags), stream)
@@ -280,9 +280,10 @@ fd_status fd_accept_sample(const void* target_logits, const void* draft_logits, 
   return FD_OK;
 }
 
-fd_status fd_profile_begin(int32_t max_calls) {
+fd_status fd_profile_begin(int32_t max_calls, int32_t stride) {
   if (g_prof_events) return fail(FD_ERR_INVALID_ARG, "profiling already on");
   if (max_calls <= 0 || max_calls > (1 << 20)) return fail(FD_ERR_INVALID_ARG, "max_calls out of range");
+  if (stride <= 0) return fail(FD_ERR_INVALID_ARG, "stride must be positive");
   g_prof_events = new hipEvent_t[2 * (size_t)max_calls];
   for (int i = 0; i < 2 * max_calls; ++i)
     if (hipEventCreate(&g_prof_events[i]) != hipSuccess) {
@@ -290,7 +291,7 @@ fd_status fd_profile_begin(int32_t max_calls) {
       delete[] g_prof_events; g_prof_events = nullptr;
       return fail(FD_ERR_HIP, "hipEventCreate failed");
     }
-  g_prof_cap = max_calls; g_prof_used = 0;
+  g_prof_cap = max_calls; g_prof_used = 0; g_prof_stride = stride; g_prof_seen = 0;
   return FD_OK;
 }
 

@@ -90,7 +90,7 @@ def load() -> C.CDLL:
     lib.fd_select_branch.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3
     lib.fd_last_error.restype = C.c_char_p
     lib.fd_profile_begin.restype = C.c_int
-    lib.fd_profile_begin.argtypes = [C.c_int32]
+    lib.fd_profile_begin.argtypes = [C.c_int32, C.c_int32]
     lib.fd_profile_end.restype = C.c_int32
     lib.fd_profile_end.argtypes = [C.POINTER(C.c_float), C.c_int32]
     lib.fd_stream_copy.restype = C.c_int
@@ -213,8 +213,8 @@ def fd_accept_sample(target_logits, draft_logits, row_indptr, input_tokens, u_ac
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def fd_profile_begin(max_calls: int) -> None:
-    _check(load().fd_profile_begin(max_calls))
+def fd_profile_begin(max_calls: int, stride: int = 1) -> None:
+    _check(load().fd_profile_begin(max_calls, stride))
 
 
 def fd_profile_end(capacity: int):
