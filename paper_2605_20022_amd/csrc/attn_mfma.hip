@@ -86,8 +86,8 @@ struct MfmaSched {
   int num_wgs;        // persistent work-groups launched
   int min_share;      // automatic shares are never smaller than this many tiles
   int fixed_share;    // > 0: tiles per work-group asked for by the caller
-  float* part_acc;    // [2 * num_wgs][ROWS_WG][D]
-  float* part_ml;     // [2 * num_wgs][ROWS_WG][2]
+  unsigned short* part_acc;   // [2 * num_wgs][ROWS_WG][D] fp16: the un-normalised output row divided by its largest magnitude
+  float* part_ml;             // [2 * num_wgs][ROWS_WG][4]: running maximum (base 2), row sum, that largest magnitude, unused
   int4* entries;      // [num_wgs]: the split item that ends in this work-group: (first packed row, head | row block << 16, tile rows, first slot); first < 0: none
 };
 
@@ -99,6 +99,20 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
   f32x2 f = {lo, hi};
   bf16x2 b = __builtin_convertvector(f, bf16x2);      // round to nearest even
   return __builtin_bit_cast(unsigned, b);
+}
+
+__device__ __forceinline__ unsigned pack_f16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  f32x2 f = {lo, hi};
+  f16x2 b = __builtin_convertvector(f, f16x2);        // round to nearest even
+  return __builtin_bit_cast(unsigned, b);
+}
+__device__ __forceinline__ void unpack_f16x4(u32x2 w, float (&x)[4]) {
+  typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+  const f16x4 hv = __builtin_bit_cast(f16x4, w);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) x[e] = (float)hv[e];
 }
 
 // Tiles of one item of this sequence, and how many items (heads x row blocks) it has.
@@ -717,17 +731,29 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
             }
           if (p.lse && h == 0)
             p.lse[(long long)(s.row0 + nn) * p.Hq + hq] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
-        } else {                                  // split partial for the combine kernel
+        } else {
+          // split partial for the combine kernel: the row scaled to [-1, 1] in fp16 (rounding 2^-11 of
+          // the row's largest entry, a quarter of what the bf16 result carries) plus (max, sum, scale)
+          float amax = 0.f;
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(o[b][i]));
+          amax = fmaxf(amax, __shfl_xor(amax, 32));
+          const float rs = amax > 0.f ? 1.0f / amax : 0.f;
           const long long ps = (long long)slot * ROWS_WG + trow;
-          float* ap = sc_.part_acc + ps * MF_D + 4 * h;
+          unsigned short* ap = sc_.part_acc + ps * MF_D + 4 * h;
 #pragma unroll
           for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-              f32x4 wv = {o[b][4 * a], o[b][4 * a + 1], o[b][4 * a + 2], o[b][4 * a + 3]};
-              *reinterpret_cast<f32x4*>(ap + 32 * b + 8 * a) = wv;
+              u32x2 wv = {pack_f16x2(o[b][4 * a] * rs, o[b][4 * a + 1] * rs), pack_f16x2(o[b][4 * a + 2] * rs, o[b][4 * a + 3] * rs)};
+              *reinterpret_cast<u32x2*>(ap + 32 * b + 8 * a) = wv;
             }
-          if (h == 0) { sc_.part_ml[ps * 2] = m_run; sc_.part_ml[ps * 2 + 1] = l_tot; }
+          if (h == 0) {
+            f32x4 ml4 = {m_run, l_tot, amax, 0.f};
+            *reinterpret_cast<f32x4*>(sc_.part_ml + ps * 4) = ml4;
+          }
         }
       }
     }
@@ -771,49 +797,51 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
   if (row0 + nn >= p.total_rows) return;
   const int np = wl - wf + 1;                     // pieces: slot first_slot, then 2 (wf + 1) .. 2 wl
-  auto ml_of = [&](int pi) -> const float* {
+  auto ml_of = [&](int pi) -> const f32x4* {               // (max, sum, scale, -)
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
-    return sc_.part_ml + (slot * ROWS_WG + trow) * 2;
+    return reinterpret_cast<const f32x4*>(sc_.part_ml + (slot * ROWS_WG + trow) * 4);
   };
-  auto acc_of = [&](int pi) -> const f32x4* {
+  auto acc_of = [&](int pi) -> const u32x2* {               // four fp16 columns of the scaled row
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
-    return reinterpret_cast<const f32x4*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + l32;
+    return reinterpret_cast<const u32x2*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + l32;
   };
   f32x4 num = {0.f, 0.f, 0.f, 0.f};
   float den = 0.f, M = -INFINITY;
-  auto add_piece = [&](float mc, float lc, const f32x4& a) {
-    const float wgt = mc == -INFINITY ? 0.f : exp2f(mc - M);
+  auto add_piece = [&](const f32x4& ml, const u32x2& a) {
+    const float wgt = ml[0] == -INFINITY ? 0.f : exp2f(ml[0] - M);
+    const float wa = wgt * ml[2];
+    float x[4]; unpack_f16x4(a, x);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) num[e] = fmaf(wgt, a[e], num[e]);
-    den = fmaf(wgt, lc, den);
+    for (int e = 0; e < 4; ++e) num[e] = fmaf(wa, x[e], num[e]);
+    den = fmaf(wgt, ml[1], den);
   };
   if (np <= 4) {
     // the usual case: everything is requested at once, one memory latency
-    float mc[4], lc[4]; f32x4 a[4];
+    f32x4 ml[4]; u32x2 a[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int pu = min(u, np - 1);
-      const float* ml = ml_of(pu);
-      mc[u] = u < np ? ml[0] : -INFINITY; lc[u] = ml[1]; a[u] = *acc_of(pu);
+      ml[u] = *ml_of(pu); a[u] = *acc_of(pu);
+      if (u >= np) ml[u][0] = -INFINITY;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) M = fmaxf(M, mc[u]);
+    for (int u = 0; u < 4; ++u) M = fmaxf(M, ml[u][0]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) add_piece(mc[u], lc[u], a[u]);
+    for (int u = 0; u < 4; ++u) add_piece(ml[u], a[u]);
   } else {
     // many pieces (a long item spread over many work-groups): eight at a time, all of a batch
     // requested together, with a running maximum (the sums are rescaled when it grows)
     for (int p0 = 0; p0 < np; p0 += 8) {
-      float mc[8], lc[8]; f32x4 a[8];
+      f32x4 ml[8]; u32x2 a[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int pu = min(p0 + u, np - 1);
-        const float* ml = ml_of(pu);
-        mc[u] = p0 + u < np ? ml[0] : -INFINITY; lc[u] = ml[1]; a[u] = *acc_of(pu);
+        ml[u] = *ml_of(pu); a[u] = *acc_of(pu);
+        if (p0 + u >= np) ml[u][0] = -INFINITY;
       }
       float Mb = M;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) Mb = fmaxf(Mb, mc[u]);
+      for (int u = 0; u < 8; ++u) Mb = fmaxf(Mb, ml[u][0]);
       if (Mb > M) {
         const float r = M == -INFINITY ? 0.f : exp2f(M - Mb);
 #pragma unroll
@@ -822,7 +850,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
         M = Mb;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) add_piece(mc[u], lc[u], a[u]);
+      for (int u = 0; u < 8; ++u) add_piece(ml[u], a[u]);
     }
   }
   const float inv = den > 0.f ? 1.0f / den : 0.f;
@@ -861,8 +889,8 @@ int attn_mfma_num_wgs() {
 // Workspace bytes for (num_wgs, rows per work-group); offsets of the (m, l) array and the entries.
 size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries) {
   auto al = [](size_t x) { return (x + 255) / 256 * 256; };
-  size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(float));
-  size_t ml = al((size_t)2 * num_wgs * rows_wg * 2 * sizeof(float));
+  size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(unsigned short));
+  size_t ml = al((size_t)2 * num_wgs * rows_wg * 4 * sizeof(float));
   size_t en = al((size_t)num_wgs * sizeof(int4));
   if (off_ml) *off_ml = acc;
   if (off_entries) *off_entries = acc + ml;
@@ -881,7 +909,7 @@ static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaS
   size_t off_ml, off_en;
   attn_mfma_workspace(sc.num_wgs, rows_wg, &off_ml, &off_en);
   char* base = reinterpret_cast<char*>(workspace);
-  sc.part_acc = reinterpret_cast<float*>(base);
+  sc.part_acc = reinterpret_cast<unsigned short*>(base);
   sc.part_ml = reinterpret_cast<float*>(base + off_ml);
   sc.entries = reinterpret_cast<int4*>(base + off_en);
 }
