@@ -159,6 +159,26 @@ def test_thousands_of_sequences(fd, B, kv, dtype, flags):
         _check(fd, inp, dtype, f"many B={B} kv={kv} {dtype} flags={flags} chunk={chunk}", kv_chunk=chunk, flags=flags)
 
 
+def test_split_partials_hold_large_values(fd):
+    """Items cut across work-groups leave their partial rows in 16 bits, scaled by the row's largest
+    entry: values far outside fp16's range must pass through unharmed.  Attention is linear in V and
+    a power-of-two factor is exact in every step, so the outputs are those of the unscaled call with
+    the exponent moved, bit for bit - and the unscaled call is checked against the oracle."""
+    w = _wl("bigv", "bf16", 3, 8, 2, 128, 16, (300, 900), (2, 6), 5, seed=61)
+    inp = W.make_attention_inputs(w)
+    base = _check(fd, inp, "bf16", "large values: unscaled", kv_chunk=128)        # shares of two tiles: every item is split
+    out0, _ = AttnCall(fd, inp, kv_chunk=128).run()
+    big = dict(inp)
+    for name in ("v_cache", "v_new"):
+        bits = inp[name].copy()
+        nz = (bits & 0x7FFF) != 0
+        bits[nz] = bits[nz] + np.uint16(20 << 7)                                  # x 2^20 (about 1e6, fp16 ends at 65504)
+        big[name] = bits
+    out1, _ = AttnCall(fd, big, kv_chunk=128).run()
+    assert np.isfinite(out1).all() and np.abs(out1).max() > 65504
+    assert np.array_equal(out1, out0 * np.float32(2.0 ** 20))
+
+
 def test_par4_full_parallel_mode(fd):
     w, _ = W.CONFIGS["par4"]
     inp = W.make_attention_inputs(w)
