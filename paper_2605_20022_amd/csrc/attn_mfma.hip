@@ -9,8 +9,8 @@
 // the same number of bytes whatever the length mix of the batch.  A share is walked as a
 // sequence of *pieces* (runs of tiles inside one item).  A piece that covers a whole item is
 // normalised and stored; an item cut by a share boundary leaves one split partial (base-2
-// running max, sum, un-normalised O) per work-group that touched it, and the work-group in
-// which it ends leaves an entry for the combine kernel below.
+// running max, sum, un-normalised O as fp16 rows scaled by their largest entry) per work-group
+// that touched it, and the work-group in which it ends leaves an entry for the combine kernel below.
 //
 // Streaming of one tile by the four waves of a work-group:
 //   page ids           scalar loads, one tile ahead (they are uniform across the work-group)
