@@ -189,12 +189,15 @@ def select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis
 
 
 def append_accepted_kv(k_cache, v_cache, k_new, v_new, page_indptr, page_indices, kv_len, row_indptr,
-                       accept_len, *, page_size: int):
+                       verify_len, accept_len, *, page_size: int):
     """Make the verified rows part of the clean prefix (Sec. 4.3, decoupled execution: the KV cache
     written by target verification is what the next draft step reuses).
 
     Sequence i commits its anchor row and its first accept_len[i] drafts, i.e. new rows
-    0 .. accept_len[i] (the bonus token has no K/V yet: it is the next step's anchor).  Row j goes
+    0 .. accept_len[i] (the bonus token has no K/V yet: it is the next step's anchor).  Only verify
+    rows can be committed: mask tokens must stay invisible to the clean prefix (Sec. 4.1), so a
+    sequence with no verify row (a mask-only draft pass, Sec. 4.3) commits nothing and
+    accept_len[i] must stay below verify_len[i].  Row j goes
     to logical position kv_len[i] + j: page page_indices[page_indptr[i] + pos // page_size], slot
     pos % page_size.  Works on copies; returns (k_cache, v_cache, new kv_len).  Arrays keep their
     dtype (bf16 bit patterns are moved as they are).
@@ -203,11 +206,12 @@ def append_accepted_kv(k_cache, v_cache, k_new, v_new, page_indptr, page_indices
     new_len = np.array(kv_len, dtype=np.int32, copy=True)
     for i in range(len(kv_len)):
         r0, n = int(row_indptr[i]), int(row_indptr[i + 1]) - int(row_indptr[i])
-        if n == 0:
+        k = int(verify_len[i])
+        if n == 0 or k == 0:
             continue
         take = int(accept_len[i]) + 1
-        if take > n:
-            raise ValueError("more rows committed than the sequence has")
+        if take < 1 or take > k:
+            raise ValueError("only the sequence's verify rows can be committed")
         pages = np.asarray(page_indices[int(page_indptr[i]):int(page_indptr[i + 1])])
         for j in range(take):
             pos = int(kv_len[i]) + j

@@ -53,7 +53,7 @@ def test_append_matches_oracle(fd, dtype, D, ps):
     assert int(call.status.item()) == 0
     kc, vc, ref_len = oa.append_accepted_kv(inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
                                             inp["page_indptr"], inp["page_indices"], inp["kv_len"],
-                                            inp["row_indptr"], acc, page_size=ps)
+                                            inp["row_indptr"], inp["verify_len"], acc, page_size=ps)
     as_bits = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if dtype == "bf16" else (lambda t: t.cpu().numpy())
     assert np.array_equal(as_bits(call.d["k_cache"]), kc)
     assert np.array_equal(as_bits(call.d["v_cache"]), vc)
@@ -100,7 +100,7 @@ def test_two_steps_of_the_loop(fd):
     assert_attn_close(out1, ref1, "bf16", "loop step 1")
     fd.fd_append_kv(call.args, torch.from_numpy(acc).cuda(), call.d["kv_len"])
     kc, vc, len2 = oa.append_accepted_kv(inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"], inp["page_indptr"],
-                                         inp["page_indices"], inp["kv_len"], inp["row_indptr"], acc, page_size=16)
+                                         inp["page_indices"], inp["kv_len"], inp["row_indptr"], inp["verify_len"], acc, page_size=16)
     # step 2: new rows drawn afresh, same row layout; the device call reuses the (now longer) cache
     rng = np.random.default_rng(7)
     step2 = dict(inp, k_cache=kc, v_cache=vc, kv_len=len2)

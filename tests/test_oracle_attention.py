@@ -373,7 +373,7 @@ def test_append_accepted_kv_then_attend_equals_attending_with_the_rows_as_new_ro
     base, _ = _run(c)
     acc = [2, 0]
     kc, vc, new_len = oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"],
-                                            c["page_indices"], c["kv_len"], c["row_indptr"], acc, page_size=ps)
+                                            c["page_indices"], c["kv_len"], c["row_indptr"], c["verify_len"], acc, page_size=ps)
     assert new_len.tolist() == [5 + 3, 10 + 1]
     # untouched slots keep their values
     assert (kc != c["k_cache"]).any(axis=(1, 3)).sum() == 4          # 3 + 1 (page, slot) pairs rewritten
@@ -389,6 +389,34 @@ def test_append_accepted_kv_then_attend_equals_attending_with_the_rows_as_new_ro
                  q=c["q"][row:row + 1], k_new=c["k_new"][row:row + 1], v_new=c["v_new"][row:row + 1])
         got, _ = _run(d)
         np.testing.assert_allclose(got[0], base[row], atol=1e-12)
-    with pytest.raises(ValueError):                                   # more rows than the sequence has
-        oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"], c["page_indices"],
-                              c["kv_len"], c["row_indptr"], [6, 0], page_size=ps)
+    for bad in ([6, 0], [4, 0], [0, 3], [-1, 0]):                     # only verify rows (4 and 3 of them) can be committed
+        with pytest.raises(ValueError):
+            oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"], c["page_indices"],
+                                  c["kv_len"], c["row_indptr"], c["verify_len"], bad, page_size=ps)
+    # the largest legal count commits every verify row and never a mask row: the cache slots that
+    # changed hold exactly the verify rows' keys
+    kc2, _, len2 = oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"],
+                                         c["page_indices"], c["kv_len"], c["row_indptr"], c["verify_len"], [3, 2], page_size=ps)
+    assert len2.tolist() == [5 + 4, 10 + 3]
+    assert (kc2 != c["k_cache"]).any(axis=(1, 3)).sum() == 7
+
+
+def test_append_skips_sequences_without_verify_rows():
+    """A mask-only draft pass (Sec. 4.3, decoupled execution) has k = 0: nothing of it may reach the
+    clean cache, whatever accept_len says (the acceptance calls return 0 for such a sequence)."""
+    ps = 4
+    c = _rand_case(12, B=2, Ls=(6, 3), ks=(0, 2), ms=(3, 2), ps=ps)
+    P0 = c["k_cache"].shape[0]
+    grow = np.random.default_rng(3).standard_normal((2,) + c["k_cache"].shape[1:])
+    c["k_cache"] = np.concatenate([c["k_cache"], grow]); c["v_cache"] = np.concatenate([c["v_cache"], grow])
+    pages, indptr = [], [0]
+    for i in range(2):
+        pages += list(c["page_indices"][c["page_indptr"][i]:c["page_indptr"][i + 1]]) + [P0 + i]
+        indptr.append(len(pages))
+    c["page_indices"] = np.array(pages, dtype=np.int32); c["page_indptr"] = np.array(indptr, dtype=np.int32)
+    kc, vc, new_len = oa.append_accepted_kv(c["k_cache"], c["v_cache"], c["k_new"], c["v_new"], c["page_indptr"],
+                                            c["page_indices"], c["kv_len"], c["row_indptr"], c["verify_len"], [0, 1], page_size=ps)
+    assert new_len.tolist() == [6, 3 + 2]
+    pg0 = c["page_indices"][c["page_indptr"][0]:c["page_indptr"][1]]
+    assert np.array_equal(kc[pg0], c["k_cache"][pg0]) and np.array_equal(vc[pg0], c["v_cache"][pg0])
+    assert (kc != c["k_cache"]).any(axis=(1, 3)).sum() == 2
