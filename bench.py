@@ -23,9 +23,13 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+ATTN_KERNELS = "attn_mfma_kernel + attn_mfma_combine_kernel (every kernel of the attention call)"
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 COLD_FOOTPRINT = 1.25e9         # bytes of distinct copies a rotating input must span
-PROFILE_STRIDE = 8               # every how many steps of the timed region the streaming kernel is event-bracketed
+MIN_KERNEL_SAMPLES = 20         # attention launches that are event-bracketed, whatever --steps is
+
+
+ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq_draft", "par4", "par_b1", "par_b2", "q3_1p7b", "q3_14b", "q3_32b"]
 
 
 def log(*a):
@@ -37,7 +41,7 @@ class Step:
 
     def __init__(self, fd, name, torch):
         from paper_2605_20022_amd import workloads as W
-        from tests.gpu_harness import AttnCall, to_dev
+        from paper_2605_20022_amd.devcall import AttnCall, to_dev
         self.fd, self.torch, self.name = fd, torch, name
         w, a = W.CONFIGS[name]
         self.w, self.a = w, a
@@ -130,31 +134,42 @@ class Step:
         for a in self.attn_args:
             b = self.fd.fd_attn_args.from_buffer_copy(a); b.kv_len = short.data_ptr(); args.append(b)
         for i in range(5):
-            self.fd.fd_append_kv(args[i % len(args)], acc, out_len)
+            self.fd.fd_append_kv(args[i % len(args)], *self.pools[i % len(args)], acc, out_len)
         torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         for i, (s, e) in enumerate(evs):
-            s.record(); self.fd.fd_append_kv(args[i % len(args)], acc, out_len); e.record()
+            s.record(); self.fd.fd_append_kv(args[i % len(args)], *self.pools[i % len(args)], acc, out_len); e.record()
         torch.cuda.synchronize()
         ts = sorted(s.elapsed_time(e) for s, e in evs)
         rows = int((acc + 1).sum().item())
         return {"append_us": round(ts[len(ts) // 2] * 1e3, 2), "append_rows": rows}
 
-    def timed(self, steps, warmup, profile_kernel=False, stride=PROFILE_STRIDE):
+    def timed(self, steps, warmup):
+        """Wall-clock time of `steps` whole steps, nothing else on the stream."""
         torch = self.torch
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
-        if profile_kernel:
-            # an event pair costs the stream about 5 us: bracket every 8th launch of the timed region
-            self.fd.fd_profile_begin((steps + stride - 1) // stride, stride)
         t0 = time.perf_counter()
         for _ in range(steps):
             self.step()
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        kern_ms = self.fd.fd_profile_end(steps) if profile_kernel else []
-        return dt / steps * 1e3, kern_ms
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def timed_kernels(self, steps):
+        """The same loop of whole steps once more, with a HIP event pair on the launching stream
+        (torch's current stream, which the binding hands to the library) around the attention call of
+        every step: the time of the call's kernels, K1 + K2 where it has two.  A pair costs the stream
+        a few microseconds, which is why the wall-clock pass above runs without them."""
+        torch = self.torch
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for s, e in evs:
+            s.record(); self.attn(); e.record()
+            if self.acc is not None:
+                self.accept()
+            self.i += 1
+        torch.cuda.synchronize()
+        return [s.elapsed_time(e) for s, e in evs]
 
     def timed_parts(self, steps, warmup):
         """Event-bracketed time of the attention call alone and the acceptance call alone."""
@@ -211,12 +226,13 @@ def time_select_branch(fd, torch, batch=128, blocks=16, block_len=15, steps=50):
     nblocks = torch.full((B,), nb, dtype=torch.int32, device="cuda")
     acc = torch.randint(0, nb, (B,), dtype=torch.int32, device="cuda")
     out = torch.zeros(B, mb, dtype=torch.int32, device="cuda")
+    fv = torch.ones(B, dtype=torch.int32, device="cuda")          # full parallel mode: block 0 saw the anchor only
     for _ in range(5):
-        fd.fd_select_branch(toks, indptr, nblocks, acc, out)
+        fd.fd_select_branch(toks, indptr, nblocks, acc, out, first_vis=fv)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     for s, e in evs:
-        s.record(); fd.fd_select_branch(toks, indptr, nblocks, acc, out); e.record()
+        s.record(); fd.fd_select_branch(toks, indptr, nblocks, acc, out, first_vis=fv); e.record()
     torch.cuda.synchronize()
     ts = sorted(s.elapsed_time(e) for s, e in evs)
     return {"batch": B, "blocks": nb, "block_len": mb, "call_us": round(ts[len(ts) // 2] * 1e3, 2)}
@@ -226,7 +242,7 @@ def cpu_baseline(name, budget_s=20.0):
     """The oracle, as it stands, on a bounded sample of the same workload: whole sequences are
     added (shortest first would bias; seeded order is used) until about budget_s of CPU time."""
     from paper_2605_20022_amd import workloads as W
-    from tests.gpu_harness import oracle_attention, subset_inputs
+    from oracle import attention as oracle_attn
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -242,9 +258,11 @@ def cpu_baseline(name, budget_s=20.0):
     order = np.random.default_rng(0).permutation(w.batch)
     done_bytes, spent, used = 0, 0.0, 0
     for i in order:
-        sub = subset_inputs(inp, [int(i)])
+        sub = W.subset_inputs(inp, [int(i)])
         t0 = time.perf_counter()
-        oracle_attention(sub)
+        oracle_attn.verify_draft_attention(
+            sub["q"], sub["k_new"], sub["v_new"], sub["k_cache"], sub["v_cache"], sub["page_indptr"], sub["page_indices"],
+            sub["kv_len"], sub["row_indptr"], sub["verify_len"], None, sub.get("mask_blocks"), page_size=w.page_size)
         if a is not None:
             r0, r1 = int(indptr[i]), int(indptr[i + 1])
             toks = np.zeros(r1 - r0, dtype=np.int32)    # the oracle's cost does not depend on the tokens
@@ -279,7 +297,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4", "q3_1p7b", "q3_14b", "q3_32b"])
+    ap.add_argument("--workload", default="cfg3", choices=ALL_WORKLOADS)
     ap.add_argument("--all-configs", dest="all_configs", action="store_true", default=True,
                     help="also report every configuration in per_config (default)")
     ap.add_argument("--headline-only", dest="all_configs", action="store_false",
@@ -309,14 +327,15 @@ def main():
         print(json.dumps({"draft_select": time_draft_select(fd, torch, steps=args.steps)}), flush=True)
         return
     if args.copy_probe:
+        from paper_2605_20022_amd import probes
         n = 1 << 30
         src = torch.ones(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
         for _ in range(3):
-            fd.fd_stream_copy(src, dst)
+            probes.stream_copy(src, dst)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            fd.fd_stream_copy(src, dst)
+            probes.stream_copy(src, dst)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
         print(json.dumps({"probe": "stream_copy", "bytes_read": n, "bytes_written": n, "launches": args.steps + 3,
@@ -324,9 +343,9 @@ def main():
         return
 
     if args.read_probe:
-        from paper_2605_20022_amd import workloads as W
+        from paper_2605_20022_amd import probes, workloads as W
         res = []
-        sums = torch.empty(fd.STREAM_READ_SUMS, dtype=torch.int32, device="cuda")
+        sums = torch.empty(probes.STREAM_READ_SUMS, dtype=torch.int32, device="cuda")
         for name in ("cfg3", "cfg5", "cfg4"):
             w = W.CONFIGS[name][0]
             n = W.kv_bytes(w, W.make_lengths(w)["kv_len"]) // 32768 * 32768
@@ -334,9 +353,9 @@ def main():
             bufs = [torch.ones(n // 4, dtype=torch.int32, device="cuda") for _ in range(pools)]
             ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
             for i in range(3):
-                fd.fd_stream_read(bufs[i % pools], sums)
+                probes.stream_read(bufs[i % pools], sums)
             for i, (e0, e1) in enumerate(ev):
-                e0.record(); fd.fd_stream_read(bufs[i % pools], sums); e1.record()
+                e0.record(); probes.stream_read(bufs[i % pools], sums); e1.record()
             torch.cuda.synchronize()
             us = np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in ev])
             res.append({"bytes_of": name, "bytes": n, "launches": args.steps, "us_mean": round(float(us.mean()), 2),
@@ -346,11 +365,12 @@ def main():
         return
 
     st = Step(fd, args.workload, torch)
-    ms_per_step, kern_ms = st.timed(args.steps, args.warmup, profile_kernel=True)
+    ms_per_step = st.timed(args.steps, args.warmup)
+    kern_ms = st.timed_kernels(max(args.steps, MIN_KERNEL_SAMPLES))
     parts = st.timed_parts(min(args.steps, 100), 5)
-    kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else None
+    kern_avg_ms = float(np.mean(kern_ms))
     value = st.kv_bytes / (ms_per_step * 1e-3) / 1e9
-    achieved = st.kv_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_avg_ms else None
+    achieved = st.kv_bytes / (kern_avg_ms * 1e-3) / 1e9
     out = {
         "metric": "verify+draft attn: KV GB/s & % HBM peak; acceptance seqs/s at vocab 151936",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -364,12 +384,13 @@ def main():
                    "kv_pools_rotated": len(st.pools)},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "attn_ms": parts.get("attn"), "accept_ms": parts.get("accept"),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 2) if achieved else None, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4) if achieved else None,
-                     "traffic": read_traffic(args.workload), "kernel": "attn_mfma_kernel",
-                     "kernel_avg_ms": round(kern_avg_ms, 5) if kern_avg_ms else None,
-                     "kernel_launches_timed": len(kern_ms), "event_stride": PROFILE_STRIDE,
-                     "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2) if kern_avg_ms else None},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": read_traffic(args.workload), "traffic_source": "committed rocprofv3 --pmc summary under profiles/",
+                     "kernel": ATTN_KERNELS,
+                     "kernel_avg_ms": round(kern_avg_ms, 5), "kernel_min_ms": round(float(np.min(kern_ms)), 5),
+                     "kernel_launches_timed": len(kern_ms),
+                     "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2)},
     }
     if "accept" in parts:
         out["accept_seqs_per_s"] = round(st.w.batch / (parts["accept"]["median_ms"] * 1e-3), 1)
@@ -379,15 +400,16 @@ def main():
 
     if args.all_configs:
         per = {}
-        for name in ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "par4", "q3_1p7b", "q3_14b", "q3_32b"]:
+        for name in ALL_WORKLOADS:
             s2 = Step(fd, name, torch)
             n = 50
-            _, km = s2.timed(n, 5, profile_kernel=True, stride=1)
+            s2.timed(5, 5)
+            km = s2.timed_kernels(n)
             p2 = s2.timed_parts(n, 3)
             k_ms = float(np.mean(km))
-            per[name] = {"kv_MB": round(s2.kv_bytes / 1e6, 2), "kernel_us": round(k_ms * 1e3, 2),
-                         "kernel_kv_GBps": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9, 1),
-                         "kernel_frac_hbm_peak": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            per[name] = {"kv_MB": round(s2.kv_bytes / 1e6, 2), "kernels_us": round(k_ms * 1e3, 2),
+                         "kernels_kv_GBps": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9, 1),
+                         "kernels_frac_hbm_peak": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                          "attn_call_us": round(p2["attn"]["median_ms"] * 1e3, 2),
                          "mfma_tflops": round(s2.flops / (k_ms * 1e-3) / 1e12, 2)}
             if "accept" in p2:

@@ -15,7 +15,9 @@
  *   - Plain C.  Every pointer marked "device" is a HIP device pointer on the
  *     current device; pointers marked "host" are ordinary host memory.
  *   - The caller owns every buffer.  The library never allocates or frees device
- *     memory, never synchronises the stream, and never writes the KV cache.
+ *     memory and never synchronises the stream.  The KV cache is read-only to every
+ *     call except fd_append_kv, which receives it through separate, writable
+ *     pointers.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL
  *     is the default stream) and the call returns immediately.
  *   - The return value is the only host-side error channel.  Argument errors are
@@ -23,10 +25,12 @@
  *     a thread-local description of the last failure.
  *   - Device-side data that contradicts the host-side bounds (a kv_len above
  *     max_kv_len, a page id outside [0, num_pages), a page_indptr entry above
- *     page_indices_len, a token id outside the vocabulary, ...) is clamped by the
- *     kernels so that no access leaves the caller's buffers, and the matching bit
- *     is OR-ed into *status if a status word was supplied.  The numerical result
- *     of such a call is unspecified.
+ *     page_indices_len, ...) is clamped by the kernels so that no access leaves
+ *     the caller's buffers, and the matching bit is OR-ed into *status if the
+ *     call has a status word and one was supplied.  The numerical result of such
+ *     a call is unspecified.  The acceptance calls have no status word: a token
+ *     id outside [0, vocab) is never used as an index, it counts as a draft that
+ *     is not kept.
  *
  * Row convention (shared by all three calls)
  *   Sequence i feeds n_i = k_i + m_i new rows into the pass: first k_i verify
@@ -61,7 +65,6 @@ typedef enum fd_dtype { FD_F32 = 0, FD_BF16 = 1 } fd_dtype;
 #define FD_DEV_KV_LEN_RANGE   1u  /* kv_len[i] < 0 or > max_kv_len                           */
 #define FD_DEV_ROWS_RANGE     2u  /* n_i < 0, n_i > max_new_rows, k_i or v_i out of range    */
 #define FD_DEV_PAGE_RANGE     4u  /* page id outside [0, num_pages) or page list too short   */
-#define FD_DEV_TOKEN_RANGE    8u  /* token id outside [0, vocab)                             */
 
 /* fd_attn_args.flags */
 #define FD_ATTN_FORCE_GENERIC 1   /* use the scalar fp32-accumulate kernel even for bf16     */
@@ -158,6 +161,7 @@ FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream
  * For sequence i with k_i rows: accept_len[i] = r_i = number of leading
  * j in [0, k_i-2] with a_j == input_tokens[j+1]; bonus_token[i] = a_{r_i}.
  * The step commits r_i + 1 tokens.  k_i = 0 gives accept_len 0, bonus -1.
+ * A token id outside [0, vocab) equals no arg-max: the draft is not kept.
  * row_argmax     device [total_rows] or NULL: receives every a_j.
  * Values are compared exactly as stored; NaN logits are undefined.
  */
@@ -172,9 +176,11 @@ FD_API fd_status fd_accept_greedy(const void *target_logits, fd_dtype dt, int64_
  *
  * p_j = softmax(target_logits[j] / temperature), q_j = softmax(draft_logits[j] /
  * temperature); draft row j is the distribution the token fed at row j+1 was drawn
- * from (each sequence's last draft row is not read).  For j = 0 .. k_i-2 with
- * d = input_tokens[j+1]: keep d iff u_accept[j] * q_j(d) < p_j(d); stop at the first
- * row j* that fails.  The bonus token is drawn from the residual
+ * from.  Each sequence's last draft row judges no token and cannot change the result,
+ * but it is read like the others: all total_rows rows of draft_logits must be
+ * readable and free of NaN.  For j = 0 .. k_i-2 with
+ * d = input_tokens[j+1]: keep d iff u_accept[j] * q_j(d) < p_j(d) (a token id outside
+ * [0, vocab) is not kept); stop at the first row j* that fails.  The bonus token is drawn from the residual
  * max(0, p_j* - q_j*) (from p_{k_i-1} when every draft was kept; from p_j* if the
  * residual is identically zero) by inverse CDF in ascending token order: the first
  * token whose inclusive cumulative weight exceeds u_resample[j*] * total weight.
@@ -222,19 +228,24 @@ FD_API size_t fd_draft_select_workspace(int32_t total_rows, int32_t vocab);
  * args->k_new / v_new; row j is written to logical position kv_len[i] + j (page
  * page_indices[page_indptr[i] + pos / page_size], slot pos % page_size), so the sequence's
  * page list must already hold the pages for them.  The bonus token has no K/V yet: it is the
- * next step's anchor.
+ * next step's anchor.  Only verify rows are ever written (mask tokens stay invisible to the
+ * clean prefix, Sec. 4.1): a sequence with k_i = 0 -- a mask-only draft pass -- commits nothing
+ * and keeps its length.
  *   args          the fd_attn_args of the attention call that produced the rows; read here:
  *                 batch, num_kv_heads, head_dim, page_size, dtype, total_rows, max_new_rows,
- *                 num_pages, k_cache, v_cache (WRITTEN despite the const), the three strides,
- *                 page_indptr, page_indices, kv_len, row_indptr, k_new, v_new, status
- *   accept_len    device int32 [B], 0 <= accept_len[i] < n_i (sequences with n_i = 0 are skipped)
- *   kv_len_out    device int32 [B]: kv_len[i] + accept_len[i] + 1; may be args->kv_len itself
- * Out-of-range device data (a page list too short, a page id outside the pool, accept_len out of
- * range) is skipped or clamped and reported through args->status like in fd_verify_draft_attn.
- * Asynchronous on hip_stream.  Errors: FD_ERR_INVALID_ARG, FD_ERR_HIP.
+ *                 num_pages, the three strides, page_indptr, page_indices, kv_len, row_indptr,
+ *                 verify_len, k_new, v_new, status.  args->k_cache / v_cache are NOT used.
+ *   k_cache, v_cache  device, WRITTEN: the cache the rows go to, in the layout the strides
+ *                 describe (normally the buffers args->k_cache / v_cache point to)
+ *   accept_len    device int32 [B], 0 <= accept_len[i] < k_i
+ *   kv_len_out    device int32 [B]: kv_len[i] + accept_len[i] + 1 (kv_len[i] when k_i = 0);
+ *                 may be args->kv_len itself
+ * Out-of-range device data (a page list too short, a page id outside the pool, accept_len
+ * outside [0, k_i)) is skipped or clamped and reported through args->status like in
+ * fd_verify_draft_attn.  Asynchronous on hip_stream.  Errors: FD_ERR_INVALID_ARG, FD_ERR_HIP.
  */
-FD_API fd_status fd_append_kv(const fd_attn_args *args, const int32_t *accept_len, int32_t *kv_len_out,
-                              void *hip_stream);
+FD_API fd_status fd_append_kv(const fd_attn_args *args, void *k_cache, void *v_cache,
+                              const int32_t *accept_len, int32_t *kv_len_out, void *hip_stream);
 
 /*
  * Branch selection of parallel speculative decoding (Sec. 3): the forward pass prepared one
@@ -243,8 +254,11 @@ FD_API fd_status fd_append_kv(const fd_attn_args *args, const int32_t *accept_le
  *   block_tokens  device int32 [total_tokens]: the drafted tokens of every block; sequence i
  *                 owns block_indptr[i] .. block_indptr[i+1], its nb_i = mask_blocks[i] blocks
  *                 of equal length back to back
- *   first_vis     device int32 [B] or NULL (=> 1): verify rows block 0 was conditioned on
- *                 (fd_attn_args.mask_vis); block b assumed first_vis[i] + b - 1 accepted drafts
+ *   first_vis     device int32 [B] or NULL: verify rows block 0 was conditioned on, i.e. the
+ *                 attention call's mask_vis; block b assumed first_vis[i] + b - 1 accepted drafts
+ *   verify_len    device int32 [B], needed when first_vis is NULL (else may be NULL): the
+ *                 attention call's verify_len.  first_vis then takes the attention call's own
+ *                 default, max(k_i - nb_i + 1, 0), so that passing NULL to both calls pairs up
  *   accept_len    device int32 [B]: accepted drafts r_i (fd_accept_greedy / fd_accept_sample)
  *   out_tokens    device int32 [B][out_stride]: the chosen block, padded with -1
  *   out_block     device int32 [B] or NULL: index of the chosen block
@@ -254,37 +268,13 @@ FD_API fd_status fd_append_kv(const fd_attn_args *args, const int32_t *accept_le
  */
 FD_API fd_status fd_select_branch(const int32_t *block_tokens, const int32_t *block_indptr,
                                   const int32_t *mask_blocks, const int32_t *accept_len,
-                                  const int32_t *first_vis, int32_t batch, int32_t total_tokens,
+                                  const int32_t *first_vis, const int32_t *verify_len,
+                                  int32_t batch, int32_t total_tokens,
                                   int32_t out_stride, int32_t *out_tokens, int32_t *out_block,
                                   void *hip_stream);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 FD_API const char *fd_last_error(void);
-
-/*
- * Kernel timing for benchmarks.  fd_profile_begin(n, stride) creates 2n HIP events; while
- * profiling is on, every stride-th fd_verify_draft_attn call (the first one included)
- * records one (start, stop) pair around its main streaming kernel on the call's stream,
- * until n pairs are recorded.  An event costs the stream a few microseconds, so a stride
- * above 1 keeps a timed loop close to its undisturbed pace.  fd_profile_end synchronises the recorded events, writes up to
- * `capacity` durations in milliseconds to ms_out (host), destroys the events and
- * returns the number written.  Not thread-safe; off by default.
- */
-FD_API fd_status fd_profile_begin(int32_t max_calls, int32_t stride);
-FD_API int32_t   fd_profile_end(float *ms_out, int32_t capacity);
-
-/* Plain device-to-device streaming copy of `bytes` (multiple of 16, both pointers 16-byte
- * aligned), asynchronous on hip_stream.  It exists for measurement: the achievable-bandwidth
- * yard-stick, and the known-size kernel the HBM traffic counters are scaled against. */
-FD_API fd_status fd_stream_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
-
-/* Staged streaming read of `bytes` (device, multiple of 32768, 16-byte aligned), asynchronous on
- * hip_stream: the attention kernel's launch shape and load scheme with no page table and no
- * arithmetic (512 work-groups of 256 threads, 32 KB tiles staged in registers, passed through LDS
- * and read back once).  sums (device, 512 * 256 words, caller-owned) receives one 32-bit word sum
- * per thread; their total is the sum of all 32-bit words of the buffer modulo 2^32.  It exists for
- * measurement: the best a job of a given size can reach with this scheme. */
-FD_API fd_status fd_stream_read(const void *src, size_t bytes, uint32_t *sums, void *hip_stream);
 
 /* Library version string, e.g. "flexdraft-gfx950 0.1". */
 FD_API const char *fd_version(void);

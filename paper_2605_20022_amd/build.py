@@ -1,5 +1,6 @@
-"""Builds libflexdraft.so in-tree with hipcc for gfx950 (no torch extension machinery:
-the library is a plain C-ABI shared object loaded through ctypes)."""
+"""Builds libflexdraft.so (the product) and libfdprobes.so (bandwidth probes used by the
+benchmark only) in-tree with hipcc for gfx950.  No torch extension machinery: both are plain
+C-ABI shared objects loaded through ctypes."""
 from __future__ import annotations
 
 import os
@@ -11,7 +12,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexdraft.so")
-SOURCES = ["api.hip", "attn_generic.hip", "attn_mfma.hip", "accept.hip", "append.hip", "util.hip"]
+PROBES_LIB = os.path.join(HERE, "libfdprobes.so")
+SOURCES = ["api.hip", "attn_generic.hip", "attn_mfma.hip", "accept.hip", "append.hip"]
+PROBE_SOURCES = ["probes.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
     "-Wall", "-Wno-unused-result",
@@ -33,7 +36,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
     procs = []
-    for src in SOURCES:
+    for src in SOURCES + PROBE_SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         cmd = [hipcc(), *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -51,13 +54,14 @@ def build(verbose: bool = True, extra_flags=()) -> str:
             print(f"--- {src}\n{out}", flush=True)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    for lib, lib_objs in ((LIB, objs[:len(SOURCES)]), (PROBES_LIB, objs[len(SOURCES):])):
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *lib_objs]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return LIB
 
 
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
-    print("built", LIB)
+    print("built", LIB, PROBES_LIB)

@@ -601,8 +601,8 @@ __global__ __launch_bounds__(ACC_BLOCK) void draft_select_epilogue_kernel(
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(FD_WAVE) void select_branch_kernel(
     const int* __restrict__ block_tokens, const int* __restrict__ block_indptr, const int* __restrict__ mask_blocks,
-    const int* __restrict__ accept_len, const int* __restrict__ first_vis, int total_tokens, int out_stride,
-    int* __restrict__ out_tokens, int* __restrict__ out_block) {
+    const int* __restrict__ accept_len, const int* __restrict__ first_vis, const int* __restrict__ verify_len,
+    int total_tokens, int out_stride, int* __restrict__ out_tokens, int* __restrict__ out_block) {
   const int seq = blockIdx.x, lane = threadIdx.x;
   const int t0 = clampi(block_indptr[seq], 0, total_tokens);
   const int len = clampi(block_indptr[seq + 1] - t0, 0, total_tokens - t0);
@@ -612,7 +612,9 @@ __global__ __launch_bounds__(FD_WAVE) void select_branch_kernel(
   const int mb = ok ? len / nb : 0;
   int b = -1;
   if (ok) {
-    b = accept_len[seq] + 1 - (first_vis ? first_vis[seq] : 1);
+    // without first_vis: the attention call's own default, the last block sees every verify row
+    const int fv = first_vis ? first_vis[seq] : max(verify_len[seq] - nb + 1, 0);
+    b = accept_len[seq] + 1 - fv;
     b = clampi(b, 0, nb - 1);
   }
   for (int j = lane; j < out_stride; j += FD_WAVE) o[j] = j < mb ? block_tokens[t0 + b * mb + j] : -1;
@@ -620,10 +622,10 @@ __global__ __launch_bounds__(FD_WAVE) void select_branch_kernel(
 }
 
 hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, const int* mask_blocks,
-                             const int* accept_len, const int* first_vis, int batch, int total_tokens,
-                             int out_stride, int* out_tokens, int* out_block, hipStream_t st) {
+                             const int* accept_len, const int* first_vis, const int* verify_len, int batch,
+                             int total_tokens, int out_stride, int* out_tokens, int* out_block, hipStream_t st) {
   hipLaunchKernelGGL(select_branch_kernel, dim3(batch), dim3(FD_WAVE), 0, st, block_tokens, block_indptr,
-                     mask_blocks, accept_len, first_vis, total_tokens, out_stride, out_tokens, out_block);
+                     mask_blocks, accept_len, first_vis, verify_len, total_tokens, out_stride, out_tokens, out_block);
   return hipGetLastError();
 }
 

@@ -15,13 +15,14 @@ size_t draft_select_workspace_bytes(int total_rows, int vocab);
 hipError_t run_draft_select(const void* logits, int dt, long long row_stride, int vocab, float temperature,
                             float threshold, const int* row_indptr, int batch, int total_rows, int max_rows,
                             int* tokens, float* confidence, int* keep_len, void* ws, hipStream_t st);
-hipError_t run_append_kv(const AttnParams& p, int dtype, const int* accept_len, int* kv_len_out, hipStream_t st);
+hipError_t run_append_kv(const AttnParams& p, int dtype, void* k_cache, void* v_cache, const int* accept_len,
+                         int* kv_len_out, hipStream_t st);
 hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, const int* mask_blocks,
-                             const int* accept_len, const int* first_vis, int batch, int total_tokens,
-                             int out_stride, int* out_tokens, int* out_block, hipStream_t st);
+                             const int* accept_len, const int* first_vis, const int* verify_len, int batch,
+                             int total_tokens, int out_stride, int* out_tokens, int* out_block, hipStream_t st);
 int attn_mfma_tile_keys();
 int attn_mfma_rows_per_wg(int max_tile_rows);
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, hipStream_t st);
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st);
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st);
 int attn_mfma_num_wgs();
 size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries);
@@ -33,8 +34,6 @@ hipError_t run_accept_sample(const void* target, const void* draft, int dt, long
                              float temperature, const int* row_indptr, const int* toks, const float* ua,
                              const float* ur, int batch, int total_rows, int max_rows, int* accept_len,
                              int* bonus, void* ws, hipStream_t st);
-hipError_t run_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
-hipError_t run_stream_read(const void* src, size_t bytes, unsigned* sums, hipStream_t st);
 }  // namespace fd
 
 namespace {
@@ -49,21 +48,6 @@ fd_status fail(fd_status code, const char* fmt, ...) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
-// profiling state (fd_profile_begin / fd_profile_end)
-hipEvent_t* g_prof_events = nullptr;
-int g_prof_cap = 0, g_prof_used = 0, g_prof_stride = 1, g_prof_seen = 0;
-
-// Builds with -DFD_MEASURE carry two timing-only variants of the MFMA kernel (selected by bits
-// 8-9 of flags; their output is meaningless); the product build has neither.
-inline int measure_variant(int flags) {
-#ifdef FD_MEASURE
-  return (flags >> 8) & 3;
-#else
-  (void)flags;
-  return 0;
-#endif
-}
 
 struct AttnPlan {
   bool use_mfma;
@@ -192,22 +176,11 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   p.part_acc = reinterpret_cast<float*>(a->workspace);
   p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a->workspace) + plan.acc_bytes);
   p.status = a->status;
-#ifdef FD_TIMELINE
-  p.tl = reinterpret_cast<unsigned long long*>(strtoull(getenv("FD_TL_PTR") ? getenv("FD_TL_PTR") : "0", nullptr, 16));
-#endif
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  const bool prof = g_prof_events && g_prof_used < g_prof_cap && (g_prof_seen++ % g_prof_stride) == 0;
-  if (prof && hipEventRecord(g_prof_events[2 * g_prof_used], stream) != hipSuccess)
-    return fail(FD_ERR_HIP, "hipEventRecord failed");
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, measure_variant(a->flags), stream)
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, stream)
                                : fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
-  if (prof) {
-    if (hipEventRecord(g_prof_events[2 * g_prof_used + 1], stream) != hipSuccess)
-      return fail(FD_ERR_HIP, "hipEventRecord failed");
-    ++g_prof_used;
-  }
   e = plan.use_mfma ? fd::run_attn_mfma_combine(p, a->workspace, stream)
                     : fd::run_attn_combine(p, a->dtype, 0, 0, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
@@ -280,36 +253,6 @@ fd_status fd_accept_sample(const void* target_logits, const void* draft_logits, 
   return FD_OK;
 }
 
-fd_status fd_profile_begin(int32_t max_calls, int32_t stride) {
-  if (g_prof_events) return fail(FD_ERR_INVALID_ARG, "profiling already on");
-  if (max_calls <= 0 || max_calls > (1 << 20)) return fail(FD_ERR_INVALID_ARG, "max_calls out of range");
-  if (stride <= 0) return fail(FD_ERR_INVALID_ARG, "stride must be positive");
-  g_prof_events = new hipEvent_t[2 * (size_t)max_calls];
-  for (int i = 0; i < 2 * max_calls; ++i)
-    if (hipEventCreate(&g_prof_events[i]) != hipSuccess) {
-      for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof_events[j]);
-      delete[] g_prof_events; g_prof_events = nullptr;
-      return fail(FD_ERR_HIP, "hipEventCreate failed");
-    }
-  g_prof_cap = max_calls; g_prof_used = 0; g_prof_stride = stride; g_prof_seen = 0;
-  return FD_OK;
-}
-
-int32_t fd_profile_end(float* ms_out, int32_t capacity) {
-  if (!g_prof_events) return 0;
-  int n = 0;
-  for (int i = 0; i < g_prof_used; ++i) {
-    float ms = 0.f;
-    if (hipEventSynchronize(g_prof_events[2 * i + 1]) == hipSuccess &&
-        hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) == hipSuccess) {
-      if (ms_out && n < capacity) ms_out[n++] = ms;
-    }
-  }
-  for (int i = 0; i < 2 * g_prof_cap; ++i) (void)hipEventDestroy(g_prof_events[i]);
-  delete[] g_prof_events; g_prof_events = nullptr; g_prof_cap = g_prof_used = 0;
-  return n;
-}
-
 size_t fd_draft_select_workspace(int32_t total_rows, int32_t vocab) {
   if (total_rows < 0 || vocab <= 0) return 0;
   return fd::draft_select_workspace_bytes(total_rows, vocab);
@@ -342,7 +285,8 @@ fd_status fd_draft_select(const void* draft_logits, fd_dtype dt, int64_t row_str
   return FD_OK;
 }
 
-fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t* kv_len_out, void* hip_stream) {
+fd_status fd_append_kv(const fd_attn_args* a, void* k_cache, void* v_cache, const int32_t* accept_len,
+                       int32_t* kv_len_out, void* hip_stream) {
   if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
   if (a->batch < 0 || a->total_rows < 0 || a->max_kv_len < 0 || a->max_new_rows < 0 || a->num_pages < 0)
     return fail(FD_ERR_INVALID_ARG, "negative size");
@@ -362,12 +306,12 @@ fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t
       return fail(FD_ERR_HIP, "length copy failed");
     return FD_OK;
   }
-  if (!a->k_cache || !a->v_cache || !a->page_indices || !a->k_new || !a->v_new || a->num_pages == 0)
+  if (!k_cache || !v_cache || !a->page_indices || !a->k_new || !a->v_new || a->num_pages == 0)
     return fail(FD_ERR_INVALID_ARG, "k_cache, v_cache, page_indices, k_new, v_new and num_pages > 0 are needed");
   if (a->cache_stride_page < 0 || a->cache_stride_head < 0 || a->cache_stride_token < a->head_dim ||
       a->cache_stride_page % 8 || a->cache_stride_head % 8 || a->cache_stride_token % 8)
     return fail(FD_ERR_INVALID_ARG, "cache strides must be non-negative multiples of 8 elements, token stride >= head_dim");
-  if (!aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->k_cache) || !aligned16(a->v_cache))
+  if (!aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(k_cache) || !aligned16(v_cache))
     return fail(FD_ERR_INVALID_ARG, "k_new, v_new, k_cache and v_cache must be 16-byte aligned");
   if (a->max_new_rows > 65535) return fail(FD_ERR_UNSUPPORTED, "max_new_rows %d > 65535", a->max_new_rows);
   fd::AttnParams p = {};
@@ -376,49 +320,34 @@ fd_status fd_append_kv(const fd_attn_args* a, const int32_t* accept_len, int32_t
   p.page_size = a->page_size;
   p.total_rows = a->total_rows; p.max_kv_len = a->max_kv_len; p.max_new_rows = a->max_new_rows;
   p.num_pages = a->num_pages; p.page_entries = a->page_indices_len < 0 ? 0 : a->page_indices_len;
-  p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+  p.k_cache = k_cache; p.v_cache = v_cache;
   p.sp = a->cache_stride_page; p.sh = a->cache_stride_head; p.st = a->cache_stride_token;
   p.page_indptr = a->page_indptr; p.page_indices = a->page_indices; p.kv_len = a->kv_len;
   p.row_indptr = a->row_indptr; p.verify_len = a->verify_len; p.mask_vis = a->mask_vis;
   p.mask_blocks = a->mask_blocks;
   p.k_new = a->k_new; p.v_new = a->v_new;
   p.status = a->status;
-  hipError_t e = fd::run_append_kv(p, a->dtype, accept_len, kv_len_out, reinterpret_cast<hipStream_t>(hip_stream));
+  hipError_t e = fd::run_append_kv(p, a->dtype, k_cache, v_cache, accept_len, kv_len_out,
+                                   reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(FD_ERR_HIP, "append launch: %s", hipGetErrorString(e));
   return FD_OK;
 }
 
 fd_status fd_select_branch(const int32_t* block_tokens, const int32_t* block_indptr, const int32_t* mask_blocks,
-                           const int32_t* accept_len, const int32_t* first_vis, int32_t batch, int32_t total_tokens,
+                           const int32_t* accept_len, const int32_t* first_vis, const int32_t* verify_len,
+                           int32_t batch, int32_t total_tokens,
                            int32_t out_stride, int32_t* out_tokens, int32_t* out_block, void* hip_stream) {
   if (batch < 0 || total_tokens < 0 || out_stride < 0) return fail(FD_ERR_INVALID_ARG, "negative size");
   g_err[0] = 0;
   if (batch == 0) return FD_OK;
   if (!block_indptr || !mask_blocks || !accept_len || (!out_tokens && out_stride > 0) || (!block_tokens && total_tokens > 0))
     return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
-  hipError_t e = fd::run_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis, batch,
+  if (!first_vis && !verify_len)
+    return fail(FD_ERR_INVALID_ARG, "first_vis is NULL: verify_len is needed for its default");
+  hipError_t e = fd::run_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, first_vis, verify_len, batch,
                                        total_tokens, out_stride, out_tokens, out_block,
                                        reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(FD_ERR_HIP, "select_branch launch: %s", hipGetErrorString(e));
-  return FD_OK;
-}
-
-fd_status fd_stream_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
-  if (!src || !dst) return fail(FD_ERR_INVALID_ARG, "src / dst NULL");
-  if (bytes % 16 || !aligned16(src) || !aligned16(dst)) return fail(FD_ERR_INVALID_ARG, "copy must be 16-byte aligned and sized");
-  g_err[0] = 0;
-  if (bytes == 0) return FD_OK;
-  hipError_t e = fd::run_stream_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return fail(FD_ERR_HIP, "copy launch: %s", hipGetErrorString(e));
-  return FD_OK;
-}
-
-fd_status fd_stream_read(const void* src, size_t bytes, uint32_t* sums, void* hip_stream) {
-  if (!src || !sums) return fail(FD_ERR_INVALID_ARG, "src / sums NULL");
-  if (bytes % 32768 || !aligned16(src)) return fail(FD_ERR_INVALID_ARG, "read probe: bytes must be a multiple of 32768 and src 16-byte aligned");
-  g_err[0] = 0;
-  hipError_t e = fd::run_stream_read(src, bytes, sums, reinterpret_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return fail(FD_ERR_HIP, "read probe launch: %s", hipGetErrorString(e));
   return FD_OK;
 }
 

@@ -2,19 +2,22 @@
 // written by target verification is what the next draft step reuses).
 //
 // grid (row j of the sequence, sequence): the work-group copies new row j's K and V, all KV
-// heads, to logical position kv_len + j if j <= accept_len.  The lengths are updated by a second,
-// tiny kernel so that the output array may be the input array.
+// heads, to logical position kv_len + j if j <= accept_len.  Only verify rows are ever written:
+// mask tokens stay invisible to the clean prefix (Sec. 4.1), so a sequence without verify rows
+// commits nothing and accept_len is held below the number of verify rows.  The lengths are
+// updated by a second, tiny kernel so that the output array may be the input array.
 #include "fd_common.h"
 
 namespace fd {
 
 template <typename T>
-__global__ __launch_bounds__(256) void append_kv_kernel(AttnParams p, const int* __restrict__ accept_len) {
+__global__ __launch_bounds__(256) void append_kv_kernel(AttnParams p, T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                                        const int* __restrict__ accept_len) {
   const int j = blockIdx.x, seq = blockIdx.y;
   const SeqInfo s = load_seq(p, seq);                         // clamps and reports bad lengths
-  if (s.n <= 0) return;
+  if (s.k <= 0) return;
   int acc = sload(accept_len, seq);
-  if (acc < 0 || acc >= s.n) { if (j == 0 && threadIdx.x == 0) flag_status(p.status, FD_DEV_ROWS_RANGE); acc = clampi(acc, 0, s.n - 1); }
+  if (acc < 0 || acc >= s.k) { if (j == 0 && threadIdx.x == 0) flag_status(p.status, FD_DEV_ROWS_RANGE); acc = clampi(acc, 0, s.k - 1); }
   if (j > acc) return;
   // kv_len is the length BEFORE the commit; load_seq checked that the page list covers it, the rows
   // added here need their own check
@@ -28,8 +31,8 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AttnParams p, const int*
   const int nvec = p.Hkv * vec_per_head;
   const T* kn = reinterpret_cast<const T*>(p.k_new) + (long long)(s.row0 + j) * p.Hkv * p.D;
   const T* vn = reinterpret_cast<const T*>(p.v_new) + (long long)(s.row0 + j) * p.Hkv * p.D;
-  T* kc = const_cast<T*>(reinterpret_cast<const T*>(p.k_cache)) + (long long)phys * p.sp + (long long)slot * p.st;
-  T* vc = const_cast<T*>(reinterpret_cast<const T*>(p.v_cache)) + (long long)phys * p.sp + (long long)slot * p.st;
+  T* kc = k_cache + (long long)phys * p.sp + (long long)slot * p.st;
+  T* vc = v_cache + (long long)phys * p.sp + (long long)slot * p.st;
   for (int i = threadIdx.x; i < 2 * nvec; i += 256) {
     const bool is_v = i >= nvec;
     const int iv = is_v ? i - nvec : i;
@@ -44,18 +47,23 @@ __global__ __launch_bounds__(256) void append_len_kernel(AttnParams p, const int
   if (seq >= p.B) return;
   const SeqInfo s = load_seq_t<false>(p, seq);
   int add = 0;
-  if (s.n > 0) {
-    add = clampi(accept_len[seq], 0, s.n - 1) + 1;
+  if (s.k > 0) {
+    add = clampi(accept_len[seq], 0, s.k - 1) + 1;
     const int room = s.npages * p.page_size - s.L;              // rows the page list can still take
     if (add > room) add = room < 0 ? 0 : room;
   }
   kv_len_out[seq] = s.L + add;
 }
 
-hipError_t run_append_kv(const AttnParams& p, int dtype, const int* accept_len, int* kv_len_out, hipStream_t st) {
+hipError_t run_append_kv(const AttnParams& p, int dtype, void* k_cache, void* v_cache, const int* accept_len,
+                         int* kv_len_out, hipStream_t st) {
   dim3 grid(p.max_new_rows, p.B);
-  if (dtype == FD_BF16) hipLaunchKernelGGL(append_kv_kernel<bf16_t>, grid, dim3(256), 0, st, p, accept_len);
-  else hipLaunchKernelGGL(append_kv_kernel<float>, grid, dim3(256), 0, st, p, accept_len);
+  if (dtype == FD_BF16)
+    hipLaunchKernelGGL(append_kv_kernel<bf16_t>, grid, dim3(256), 0, st, p, reinterpret_cast<bf16_t*>(k_cache),
+                       reinterpret_cast<bf16_t*>(v_cache), accept_len);
+  else
+    hipLaunchKernelGGL(append_kv_kernel<float>, grid, dim3(256), 0, st, p, reinterpret_cast<float*>(k_cache),
+                       reinterpret_cast<float*>(v_cache), accept_len);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(append_len_kernel, dim3((p.B + 255) / 256), dim3(256), 0, st, p, accept_len, kv_len_out);

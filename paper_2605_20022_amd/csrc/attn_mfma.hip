@@ -142,10 +142,8 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
-// DBG (builds with -DFD_MEASURE only): 1 = stream tiles but skip the arithmetic, 2 = do the arithmetic on
-// whatever the first tile left in LDS and skip the global loads; both produce meaningless output.
 // MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
-template <int DBG, int MAXRB>
+template <int MAXRB>
 __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
   constexpr int MF_START_COST = mf_start_cost(MAXRB);
@@ -154,18 +152,6 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   __shared__ int sh_w[MF_BLOCK / 64];
   __shared__ int sh_found[12];
 
-#ifdef FD_TIMELINE
-  const unsigned long long tl0 = wall_clock64();
-  unsigned long long tl1 = 0, tl2 = 0, tl3 = 0; int tl_pieces = 0;
-#define FD_TL(x) x = wall_clock64()
-  // stamp k (0..3) of piece tl_pieces-1 (first four pieces): written straight to memory by thread 0
-#define FD_TLP(k) do { if (p.tl && tid == 0 && tl_pieces >= 1 && tl_pieces <= 4) p.tl[8 * 1024 + (size_t)w * 16 + 4 * (tl_pieces - 1) + (k)] = wall_clock64(); } while (0)
-#define FD_TLS(k) do { if (p.tl && tid == 0) p.tl[8 * 1024 + (size_t)blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
-#else
-#define FD_TL(x)
-#define FD_TLP(k)
-#define FD_TLS(k)
-#endif
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
   const int w = blockIdx.x;
@@ -203,7 +189,6 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (lane == 63) sh_w[wave] = it;
     if (tid == 0) sh_found[0] = -1;
     __syncthreads();
-    FD_TLS(12);                                    // sequence arrays arrived, scanned
     int wt = 0;
 #pragma unroll
     for (int q = 0; q < MF_BLOCK / 64; ++q) {
@@ -224,7 +209,6 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     }
     if (bad) flag_status(p.status, bad);
     __syncthreads();
-    FD_TLS(13);                                    // starting sequence known
     seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
     if (seq < 0) return;                                         // cannot happen for consistent data
     Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
@@ -481,7 +465,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(zero);
     }
     load_tile(pc, pc.tile0, id0, rA);
-    if (pc.nt > 1 && DBG != 2) load_tile(pc, pc.tile0 + 1, id1, rB);
+    if (pc.nt > 1) load_tile(pc, pc.tile0 + 1, id1, rB);
     fetch_pages(pc, pc.tile0 + 2, pg);
   };
 
@@ -493,9 +477,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #pragma unroll
   for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
   start_ids(cur, nid0, nid1);
-  FD_TLS(14);                                      // first page ids arrived (the stamp waits for them)
   start_loads(cur, ln, nid0, nid1);
-  FD_TL(tl1);
   bool have = true;
   while (have) {
     // descriptor and page ids of the piece after this one: in flight during the tile loop
@@ -531,11 +513,6 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
     store_tile(0, rA);                             // waits for the piece's first tile
     __syncthreads();
-#ifdef FD_TIMELINE
-    if (first_piece) FD_TL(tl2);
-    ++tl_pieces;
-#endif
-    FD_TLP(0);                                     // first tile of the piece is in LDS
 
     // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
     // (requested earlier) is written to the other LDS buffer and tile t+2 is requested.
@@ -543,7 +520,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       const int tau = tile0 + t;
       const bf16_t* Ks = lds + (t & 1) * MF_BUF_ELEMS;
       const bf16_t* Vs = Ks + MF_K_ELEMS;
-      if (t + 2 < nt && DBG != 2) {
+      if (t + 2 < nt) {
         load_tile(cur, tau + 2, pg, r_load);
         fetch_pages(cur, tau + 3, pg);
       }
@@ -554,7 +531,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       const int tile_end = is_new ? s.n : c1;                     // keys at or beyond are invisible
       const bool masked = is_new | (tile_base + MF_TK > tile_end);
 
-      if (DBG != 1 && wave_has_rows && kq < KQ) {
+      if (wave_has_rows && kq < KQ) {
         // S^T = K Q^T for the 32 keys of block kb
         auto compute_S = [&](int kb) -> f32x16 {
           f32x16 sc;
@@ -662,7 +639,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
         }
       }
 
-      if (t + 1 < nt && DBG != 2) store_tile((t + 1) & 1, r_store);
+      if (t + 1 < nt) store_tile((t + 1) & 1, r_store);
       __syncthreads();                           // tile t fully consumed, tile t+1 visible
     };
     for (int t = 0; t < nt; t += 2) {
@@ -670,12 +647,10 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       if (t + 1 < nt) iteration(t + 1, rA, rB);
     }
 
-    FD_TLP(1);                                     // tiles done
     // ---- next piece: get its loads going before this one is merged and stored --------------
     Lane ln_next = ln;
     if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1); }
 
-    FD_TLP(2);                                     // next piece requested
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
     f32x4* xch = reinterpret_cast<f32x4*>(lds);                    // [wave][17][64] quads: 16 of O, then (m, l)
     if (MAXRB != 4 && KQ > 1) {
@@ -758,18 +733,9 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       }
     }
     __syncthreads();                              // LDS is reused by the next piece
-    FD_TLP(3);                                     // merged and stored
     first_piece = false;
     if (have) { cur = nxt; ln = ln_next; }
   }
-#ifdef FD_TIMELINE
-  FD_TL(tl3);
-  if (p.tl && tid == 0) {
-    unsigned long long* o8 = p.tl + (size_t)w * 8;
-    o8[0] = tl0; o8[1] = tl1; o8[2] = tl2; o8[3] = tl3; o8[4] = (unsigned long long)(g1 - g0); o8[5] = tl_pieces;
-    o8[6] = __builtin_amdgcn_s_getreg(63492); o8[7] = __builtin_amdgcn_s_getreg(63508);
-  }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------
@@ -914,31 +880,24 @@ static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaS
   sc.entries = reinterpret_cast<int4*>(base + off_en);
 }
 
-template <int DBG, int MAXRB>
+template <int MAXRB>
 static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DBG, MAXRB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<MAXRB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)MF_LDS_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL((attn_mfma_kernel<DBG, MAXRB>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
+  hipLaunchKernelGGL((attn_mfma_kernel<MAXRB>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
   return hipGetLastError();
 }
 
 // `workspace` must hold attn_mfma_workspace(...) bytes; kv_chunk > 0 asks for shares of that many keys.
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, int dbg, hipStream_t st) {
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st) {
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, kv_chunk, sc, rows_wg);
-  const bool small = rows_wg == 64;
-#ifdef FD_MEASURE
-  if (dbg == 1) return small ? launch_mfma<1, 2>(p, sc, st) : launch_mfma<1, 4>(p, sc, st);
-  if (dbg == 2) return small ? launch_mfma<2, 2>(p, sc, st) : launch_mfma<2, 4>(p, sc, st);
-#else
-  (void)dbg;
-#endif
-  return small ? launch_mfma<0, 2>(p, sc, st) : launch_mfma<0, 4>(p, sc, st);
+  return rows_wg == 64 ? launch_mfma<2>(p, sc, st) : launch_mfma<4>(p, sc, st);
 }
 
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {

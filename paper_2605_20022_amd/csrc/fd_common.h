@@ -79,9 +79,6 @@ struct AttnParams {
   float* part_acc;    // [max_chunks][R][Hq][D]
   float* part_ml;     // [max_chunks][R][Hq][2]
   uint32_t* status;
-#ifdef FD_TIMELINE
-  unsigned long long* tl;   // measurement builds: [work-group][8] timestamps
-#endif
 };
 
 // SCALAR: read through the scalar path (index uniform across the wave) and report bad data

@@ -1,10 +1,21 @@
-// Measurement probes.  Plain streaming copy: the yard-stick for achievable HBM bandwidth and for scaling
-// the FETCH_SIZE / WRITE_SIZE hardware counters (it moves exactly `bytes` in and `bytes` out).  Staged
-// read: the attention kernel's launch shape and load scheme with nothing else in it, i.e. what a job of
-// a given size can reach at best.
-#include "fd_common.h"
+// Measurement probes: a library of their own (libfdprobes.so), used by the benchmark only and not part
+// of the product library or its header.  Plain streaming copy: the yard-stick for achievable HBM
+// bandwidth and for scaling the FETCH_SIZE / WRITE_SIZE hardware counters (it moves exactly `bytes` in
+// and `bytes` out).  Staged read: the attention kernel's launch shape and load scheme with nothing else
+// in it, i.e. what a job of a given size can reach at best.
+//
+//   int fdp_stream_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
+//       device pointers, 16-byte aligned, bytes a multiple of 16; asynchronous on the stream
+//   int fdp_stream_read(const void* src, size_t bytes, uint32_t* sums, void* hip_stream)
+//       bytes a multiple of 32768; sums (device, 512 * 256 words) receives one 32-bit word sum per
+//       thread, their total is the sum of all 32-bit words of the buffer modulo 2^32
+// Both return 0, 1 for a bad argument, 4 for a failed launch.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace fd {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 __global__ __launch_bounds__(256) void stream_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
   size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
@@ -80,4 +91,19 @@ hipError_t run_stream_read(const void* src, size_t bytes, unsigned* sums, hipStr
   return hipGetLastError();
 }
 
-}  // namespace fd
+}  // namespace
+
+extern "C" {
+
+__attribute__((visibility("default"))) int fdp_stream_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes % 16 || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15)) return 1;
+  if (bytes == 0) return 0;
+  return run_stream_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess ? 0 : 4;
+}
+
+__attribute__((visibility("default"))) int fdp_stream_read(const void* src, size_t bytes, uint32_t* sums, void* hip_stream) {
+  if (!src || !sums || bytes % 32768 || (reinterpret_cast<uintptr_t>(src) & 15)) return 1;
+  return run_stream_read(src, bytes, sums, reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess ? 0 : 4;
+}
+
+}  // extern "C"

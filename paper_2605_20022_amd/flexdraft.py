@@ -50,8 +50,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_profile_begin", "fd_profile_end", "fd_stream_copy", "fd_stream_read",
-           "fd_version"]
+           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_version"]
 
 
 def load() -> C.CDLL:
@@ -85,18 +84,10 @@ def load() -> C.CDLL:
     lib.fd_draft_select_workspace.restype = C.c_size_t
     lib.fd_draft_select_workspace.argtypes = [C.c_int32, C.c_int32]
     lib.fd_append_kv.restype = C.c_int
-    lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fd_select_branch.restype = C.c_int
-    lib.fd_select_branch.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3
+    lib.fd_select_branch.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 3 + [C.c_void_p] * 3
     lib.fd_last_error.restype = C.c_char_p
-    lib.fd_profile_begin.restype = C.c_int
-    lib.fd_profile_begin.argtypes = [C.c_int32, C.c_int32]
-    lib.fd_profile_end.restype = C.c_int32
-    lib.fd_profile_end.argtypes = [C.POINTER(C.c_float), C.c_int32]
-    lib.fd_stream_copy.restype = C.c_int
-    lib.fd_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-    lib.fd_stream_read.restype = C.c_int
-    lib.fd_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.fd_version.restype = C.c_char_p
     _lib = lib
     return lib
@@ -213,16 +204,6 @@ def fd_accept_sample(target_logits, draft_logits, row_indptr, input_tokens, u_ac
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def fd_profile_begin(max_calls: int, stride: int = 1) -> None:
-    _check(load().fd_profile_begin(max_calls, stride))
-
-
-def fd_profile_end(capacity: int):
-    buf = (C.c_float * capacity)()
-    n = load().fd_profile_end(buf, capacity)
-    return [buf[i] for i in range(n)]
-
-
 def fd_draft_select_workspace(total_rows: int, vocab: int) -> int:
     return int(load().fd_draft_select_workspace(total_rows, vocab))
 
@@ -241,37 +222,23 @@ def fd_draft_select(draft_logits, row_indptr, draft_tokens, keep_len, *, tempera
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def fd_append_kv(args: fd_attn_args, accept_len, kv_len_out, stream=None) -> None:
-    """Commit new rows 0 .. accept_len[i] of the call described by `args` to its paged cache."""
-    _check(load().fd_append_kv(C.byref(args), _ptr(_i32(accept_len, "accept_len")),
+def fd_append_kv(args: fd_attn_args, k_cache, v_cache, accept_len, kv_len_out, stream=None) -> None:
+    """Commit new rows 0 .. accept_len[i] of the call described by `args` to the paged cache
+    k_cache / v_cache (written; laid out as args' strides say)."""
+    _check(load().fd_append_kv(C.byref(args), _ptr(k_cache), _ptr(v_cache), _ptr(_i32(accept_len, "accept_len")),
                                _ptr(_i32(kv_len_out, "kv_len_out")), _stream(stream)))
 
 
 def fd_select_branch(block_tokens, block_indptr, mask_blocks, accept_len, out_tokens, *, first_vis=None,
-                     out_block=None, stream=None) -> None:
+                     verify_len=None, out_block=None, stream=None) -> None:
     B = accept_len.shape[0]
     _check(load().fd_select_branch(
         _ptr(_i32(block_tokens, "block_tokens")), _ptr(_i32(block_indptr, "block_indptr")),
         _ptr(_i32(mask_blocks, "mask_blocks")), _ptr(_i32(accept_len, "accept_len")),
-        None if first_vis is None else _ptr(_i32(first_vis, "first_vis")), B, block_tokens.numel(),
+        None if first_vis is None else _ptr(_i32(first_vis, "first_vis")),
+        None if verify_len is None else _ptr(_i32(verify_len, "verify_len")), B, block_tokens.numel(),
         out_tokens.shape[1], _ptr(_i32(out_tokens, "out_tokens")),
         None if out_block is None else _ptr(_i32(out_block, "out_block")), _stream(stream)))
-
-
-def fd_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
-    nbytes = src.numel() * src.element_size()
-    _check(load().fd_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
-
-
-STREAM_READ_SUMS = 512 * 256
-
-
-def fd_stream_read(src: torch.Tensor, sums: torch.Tensor, stream=None) -> None:
-    """Staged read of `src` (bytes a multiple of 32768); sums: int32/uint32 device tensor of 512 * 256 words."""
-    nbytes = src.numel() * src.element_size()
-    if sums.numel() != STREAM_READ_SUMS or sums.element_size() != 4 or not sums.is_contiguous():
-        raise ValueError("sums must be a contiguous tensor of 512 * 256 32-bit words")
-    _check(load().fd_stream_read(_ptr(src), nbytes, _ptr(sums), _stream(stream)))
 
 
 def fd_version() -> str:

@@ -122,6 +122,17 @@ CONFIGS = {
                           seed=BASE_SEED + 5, mask_blocks=0),
              None),
 }
+# Decoupled execution (Sec. 4.3): the draft step of the large-batch mode runs the mask tokens alone
+# over the cache target verification left behind -- cfg4's batch and prefix lengths (same seed, and
+# the lengths are the first thing drawn), no verify rows, one block of 16 mask tokens.
+CONFIGS["seq_draft"] = (AttnWorkload("seq_draft", "bf16", 128, 32, 8, 128, 16, (1024, 8192), (0, 0), 16, _INV_SQRT_128,
+                                     seed=BASE_SEED + 3), None)
+# Full parallel mode at the batch sizes it is used at (Sec. 4.3: batch <= 2): the anchor and 15 drafts
+# are verified while one block of 16 mask tokens is drafted per hypothetical number of accepted drafts
+# (Sec. 3: k + 1 hypotheses for k drafts) -- 16 + 16 x 16 = 272 new rows per sequence.
+for _name, _b in (("par_b1", 1), ("par_b2", 2)):
+    CONFIGS[_name] = (AttnWorkload(_name, "bf16", _b, 32, 8, 128, 16, (2048, 8192), (16, 16), 16, _INV_SQRT_128,
+                                   seed=BASE_SEED + 6, mask_blocks=0), None)
 # The other sizes of the model family the paper decodes with (Sec. 5, models table): cfg3's batch,
 # lengths and paging with the attention shapes of the public Qwen3 configurations.  All of them keep
 # D = 128 and 8 KV heads; what changes is the number of query heads per KV head.
@@ -262,3 +273,23 @@ def verify_row_indptr(lens: dict) -> np.ndarray:
     out = np.zeros(len(lens["verify_len"]) + 1, dtype=np.int32)
     out[1:] = np.cumsum(lens["verify_len"])
     return out
+
+
+def subset_inputs(inp: dict, ids) -> dict:
+    """The same problem restricted to sequences `ids` (caches and page ids untouched)."""
+    ids = list(ids)
+    rows = [np.arange(inp["row_indptr"][i], inp["row_indptr"][i + 1]) for i in ids]
+    keep = np.concatenate(rows) if rows else np.zeros(0, dtype=np.int64)
+    sub = dict(inp)
+    for k in ("q", "k_new", "v_new"):
+        sub[k] = inp[k][keep]
+    sub["kv_len"] = inp["kv_len"][ids]
+    sub["verify_len"] = inp["verify_len"][ids]
+    if inp.get("mask_blocks") is not None:
+        sub["mask_blocks"] = np.asarray(inp["mask_blocks"])[ids]
+    sub["row_indptr"] = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
+    pages = [inp["page_indices"][inp["page_indptr"][i]:inp["page_indptr"][i + 1]] for i in ids]
+    sub["page_indices"] = np.concatenate(pages).astype(np.int32) if pages else np.zeros(0, dtype=np.int32)
+    sub["page_indptr"] = np.concatenate([[0], np.cumsum([len(p) for p in pages])]).astype(np.int32)
+    sub["_rows"] = keep
+    return sub

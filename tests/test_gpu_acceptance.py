@@ -208,13 +208,46 @@ def test_select_branch_matches_oracle(fd):
         m = lens[i] // nb[i]
         assert got[i, :m].tolist() == ref[0].tolist() and (got[i, m:] == -1).all()
         assert gb[i] == min(max(acc[i] + 1 - fv[i], 0), nb[i] - 1)
-    # default first_vis = 1: block index = accepted drafts
-    fd.fd_select_branch(dev(toks), dev(indptr), dev(nb), dev(acc), out, out_block=blk)
+    # without first_vis the attention call's default applies: block 0 saw k - nb + 1 verify rows
+    k = (nb + rng.integers(-1, 4, size=B)).clip(0).astype(np.int32)     # fewer blocks than verify rows, as many, more
+    fd.fd_select_branch(dev(toks), dev(indptr), dev(nb), dev(acc), out, verify_len=dev(k), out_block=blk)
     torch.cuda.synchronize()
-    gb = blk.cpu().numpy()
+    got, gb = out.cpu().numpy(), blk.cpu().numpy()
     for i in range(B):
         if lens[i] % nb[i] == 0:
-            assert gb[i] == min(acc[i], nb[i] - 1)
+            ref = oa.select_branch(toks[indptr[i]:indptr[i + 1]], [0, lens[i]], [nb[i]], [acc[i]], [max(k[i] - nb[i] + 1, 0)])
+            m = lens[i] // nb[i]
+            assert got[i, :m].tolist() == ref[0].tolist()
+            assert gb[i] == min(max(acc[i] + 1 - max(k[i] - nb[i] + 1, 0), 0), nb[i] - 1)
+    with pytest.raises(fd.FlexDraftError):                 # neither first_vis nor verify_len
+        fd.fd_select_branch(dev(toks), dev(indptr), dev(nb), dev(acc), out, out_block=blk)
+
+
+def test_default_visibility_pairs_attention_with_branch_selection(fd):
+    """Selective verification prunes the hypotheses (Sec. 4.3, Eq. 5): fewer candidate blocks than
+    verify rows.  With the defaults of both calls (no mask_vis, no first_vis) block b is drafted
+    seeing k - nb + 1 + b verify rows, and r accepted drafts must select the block that saw r + 1 of
+    them.  Each block carries, as its 'tokens', the number of verify rows the oracle's visibility
+    rule lets it see, so the selected block names the hypothesis it was drafted under."""
+    from oracle import attention as oa
+    B, k, nb, mb = 5, 6, 3, 2
+    vis_rows = []
+    for b in range(nb):
+        vis = oa.visibility(0, k, nb * mb, k - nb + 1, nb)           # the attention call's default first_vis
+        seen = int(vis[k + b * mb, :k].sum())                        # verify rows the block's first row sees
+        vis_rows += [seen] * mb
+    toks = np.tile(np.array(vis_rows, dtype=np.int32), B)
+    indptr = np.arange(0, B * nb * mb + 1, nb * mb, dtype=np.int32)
+    acc = np.array([3, 4, 5, 0, 5], dtype=np.int32)                  # accepted drafts; r + 1 rows are clean
+    out = torch.full((B, mb), -7, dtype=torch.int32, device="cuda")
+    dev = lambda a: torch.from_numpy(a).cuda()
+    fd.fd_select_branch(dev(toks), dev(indptr), dev(np.full(B, nb, np.int32)), dev(acc), out,
+                        verify_len=dev(np.full(B, k, np.int32)))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for i in range(B):
+        want = min(max(acc[i] + 1, k - nb + 1), k)                   # hypotheses below the pruned range clamp to block 0
+        assert (got[i] == want).all(), (i, got[i], want)
 
 
 # fp32 exponentials carry ~1e-6 relative error on a confidence (the exponent's argument is

@@ -48,7 +48,7 @@ def test_append_matches_oracle(fd, dtype, D, ps):
     call = AttnCall(fd, inp)
     acc_d = torch.from_numpy(acc).cuda()
     new_len = torch.full((w.batch,), -5, dtype=torch.int32, device="cuda")
-    fd.fd_append_kv(call.args, acc_d, new_len)
+    fd.fd_append_kv(call.args, call.d["k_cache"], call.d["v_cache"], acc_d, new_len)
     torch.cuda.synchronize()
     assert int(call.status.item()) == 0
     kc, vc, ref_len = oa.append_accepted_kv(inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
@@ -60,7 +60,7 @@ def test_append_matches_oracle(fd, dtype, D, ps):
     assert np.array_equal(new_len.cpu().numpy(), ref_len)
     # in place: the output may be the input array
     call2 = AttnCall(fd, inp)
-    fd.fd_append_kv(call2.args, acc_d, call2.d["kv_len"])
+    fd.fd_append_kv(call2.args, call2.d["k_cache"], call2.d["v_cache"], acc_d, call2.d["kv_len"])
     torch.cuda.synchronize()
     assert np.array_equal(call2.d["kv_len"].cpu().numpy(), ref_len)
     assert np.array_equal(as_bits(call2.d["k_cache"]), kc)
@@ -74,16 +74,47 @@ def test_append_reports_bad_device_data(fd):
     acc = torch.zeros(3, dtype=torch.int32, device="cuda")
     out_len = torch.zeros(3, dtype=torch.int32, device="cuda")
     before = call.d["k_cache"].clone()
-    fd.fd_append_kv(call.args, acc, out_len)
+    fd.fd_append_kv(call.args, call.d["k_cache"], call.d["v_cache"], acc, out_len)
     torch.cuda.synchronize()
     assert int(call.status.item()) & 4                   # FD_DEV_PAGE_RANGE: no page for the row
     assert torch.equal(before, call.d["k_cache"])        # nothing was written
     assert np.array_equal(out_len.cpu().numpy(), inp["kv_len"])
     call.status.zero_()
-    acc[1] = 99                                          # more rows than the sequence has
-    fd.fd_append_kv(call.args, acc, out_len)
+    acc[1] = int(inp["verify_len"][1])                   # one more than the verify rows: a mask row
+    fd.fd_append_kv(call.args, call.d["k_cache"], call.d["v_cache"], acc, out_len)
     torch.cuda.synchronize()
     assert int(call.status.item()) & 2                   # FD_DEV_ROWS_RANGE
+
+
+def test_append_never_commits_mask_rows(fd):
+    """Sequences without verify rows (mask-only draft pass, Sec. 4.3) mixed with ordinary ones: the
+    former keep their pages and lengths whatever accept_len holds (the acceptance calls give 0 for
+    them); the others commit up to all k_i verify rows and never a mask row (Sec. 4.1: mask tokens
+    stay invisible to the clean prefix)."""
+    w = W.AttnWorkload("appmask", "bf16", 9, 8, 2, 128, 16, (5, 120), (0, 3), 4, 1.0, seed=84, spare_page_frac=0.2)
+    inp = _with_room(W.make_attention_inputs(w), 8)
+    k = inp["verify_len"]
+    assert (k == 0).any() and (k > 0).any()
+    acc = np.where(k > 0, k - 1, 0).astype(np.int32)     # every verify row; 0 where there is none
+    call = AttnCall(fd, inp)
+    new_len = torch.full((w.batch,), -5, dtype=torch.int32, device="cuda")
+    fd.fd_append_kv(call.args, call.d["k_cache"], call.d["v_cache"], torch.from_numpy(acc).cuda(), new_len)
+    torch.cuda.synchronize()
+    assert int(call.status.item()) == 0
+    kc, vc, ref_len = oa.append_accepted_kv(inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
+                                            inp["page_indptr"], inp["page_indices"], inp["kv_len"],
+                                            inp["row_indptr"], k, acc, page_size=16)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(bits(call.d["k_cache"]), kc) and np.array_equal(bits(call.d["v_cache"]), vc)
+    assert np.array_equal(new_len.cpu().numpy(), ref_len)
+    assert np.array_equal(ref_len[k == 0], inp["kv_len"][k == 0])
+    # an accept_len that reaches into the mask rows is clamped to the verify rows and reported
+    call2 = AttnCall(fd, inp)
+    bad = acc.copy(); bad[k > 0] += 2
+    fd.fd_append_kv(call2.args, call2.d["k_cache"], call2.d["v_cache"], torch.from_numpy(bad).cuda(), new_len)
+    torch.cuda.synchronize()
+    assert int(call2.status.item()) & 2                  # FD_DEV_ROWS_RANGE
+    assert np.array_equal(bits(call2.d["k_cache"]), kc) and np.array_equal(new_len.cpu().numpy(), ref_len)
 
 
 def test_two_steps_of_the_loop(fd):
@@ -98,7 +129,7 @@ def test_two_steps_of_the_loop(fd):
                                         inp["page_indptr"], inp["page_indices"], inp["kv_len"], inp["row_indptr"],
                                         inp["verify_len"], page_size=16)
     assert_attn_close(out1, ref1, "bf16", "loop step 1")
-    fd.fd_append_kv(call.args, torch.from_numpy(acc).cuda(), call.d["kv_len"])
+    fd.fd_append_kv(call.args, call.d["k_cache"], call.d["v_cache"], torch.from_numpy(acc).cuda(), call.d["kv_len"])
     kc, vc, len2 = oa.append_accepted_kv(inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"], inp["page_indptr"],
                                          inp["page_indices"], inp["kv_len"], inp["row_indptr"], inp["verify_len"], acc, page_size=16)
     # step 2: new rows drawn afresh, same row layout; the device call reuses the (now longer) cache

@@ -106,23 +106,35 @@ def test_widened_entry_points_validate_on_the_host():
     assert f(None, fd.FD_BF16, 100, 100, 1.0, 0.3, None, 0, 0, 0, None, None, None, None, 0, None) == 0   # empty batch
     assert f(None, fd.FD_BF16, 100, 100, 1.0, 0.3, None, 1, 1, 1, None, None, None, None, 0, None) == 1   # NULL pointers
     # branch selection
-    assert lib.fd_select_branch(None, None, None, None, None, -1, 0, 0, None, None, None) == 1
-    assert lib.fd_select_branch(None, None, None, None, None, 0, 0, 0, None, None, None) == 0
-    assert lib.fd_select_branch(None, None, None, None, None, 2, 4, 2, None, None, None) == 1
+    assert lib.fd_select_branch(None, None, None, None, None, None, -1, 0, 0, None, None, None) == 1
+    assert lib.fd_select_branch(None, None, None, None, None, None, 0, 0, 0, None, None, None) == 0
+    assert lib.fd_select_branch(None, None, None, None, None, None, 2, 4, 2, None, None, None) == 1
+    p = C.c_void_p(4096)                                  # never dereferenced: the call fails on the host
+    assert lib.fd_select_branch(p, p, p, p, None, None, 2, 4, 2, p, None, None) == 1 and b"verify_len" in lib.fd_last_error()
     # commit of accepted rows
-    assert lib.fd_append_kv(None, None, None, None) == 1
+    assert lib.fd_append_kv(None, None, None, None, None, None) == 1
     a = fd.fd_attn_args()
     a.dtype = fd.FD_BF16; a.batch = 0; a.num_kv_heads = 8; a.head_dim = 128; a.page_size = 16
-    assert lib.fd_append_kv(C.byref(a), None, None, None) == 0                   # empty batch
+    assert lib.fd_append_kv(C.byref(a), None, None, None, None, None) == 0       # empty batch
     a.batch = 2
-    assert lib.fd_append_kv(C.byref(a), None, None, None) == 1 and b"NULL" in lib.fd_last_error()
+    assert lib.fd_append_kv(C.byref(a), None, None, None, None, None) == 1 and b"NULL" in lib.fd_last_error()
     a.head_dim = 100
-    assert lib.fd_append_kv(C.byref(a), None, None, None) == 1
+    assert lib.fd_append_kv(C.byref(a), None, None, None, None, None) == 1
+
+
+def test_header_declares_only_the_methods_calls():
+    """Measurement helpers live in a library of their own, not in the product's header or exports."""
+    names = _declared_symbols()
+    assert not [n for n in names if "probe" in n or "profile" in n or "stream_" in n]
+    lib = fd.load()
+    for n in ("fd_stream_copy", "fd_stream_read", "fd_profile_begin", "fd_profile_end"):
+        assert not hasattr(lib, n)
 
 
 def test_measurement_probes_validate_on_the_host():
-    """fd_stream_copy / fd_stream_read reject NULL pointers and sizes that are not whole units."""
-    lib = fd.load()
-    assert lib.fd_stream_copy(None, None, 16, None) == 1
-    assert lib.fd_stream_read(None, 32768, None, None) == 1 and b"NULL" in lib.fd_last_error()
-    assert lib.fd_stream_read(C.c_void_p(4096), 1000, C.c_void_p(4096), None) == 1 and b"32768" in lib.fd_last_error()
+    """The benchmark's probe library rejects NULL pointers and sizes that are not whole units."""
+    from paper_2605_20022_amd import probes
+    lib = probes.load()
+    assert lib.fdp_stream_copy(None, None, 16, None) == 1
+    assert lib.fdp_stream_read(None, 32768, None, None) == 1
+    assert lib.fdp_stream_read(C.c_void_p(4096), 1000, C.c_void_p(4096), None) == 1
