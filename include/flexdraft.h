@@ -151,6 +151,22 @@ FD_API size_t fd_verify_draft_attn_workspace(const fd_attn_args *args);
 FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream);
 
 /*
+ * fd_verify_draft_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same result; args->workspace and args->workspace_bytes are ignored and
+ * the split partials go to a buffer of FD_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (every GPU the library runs on holds it until the process ends).  The call allocates and
+ * frees nothing.  A call whose fd_verify_draft_attn_workspace() exceeds FD_STATIC_SCRATCH_BYTES is
+ * rejected with FD_ERR_WORKSPACE_TOO_SMALL before anything is launched (the MFMA kernel's need is
+ * independent of batch and lengths and always fits; the fp32 kernel's grows with rows x chunks).
+ * All calls on one GPU share the one buffer: calls that may overlap on a GPU (different streams,
+ * different threads) race on it and must be serialised by the caller; calls on one stream are safe.
+ * Nothing in the buffer has to survive from call to call, and nothing in it has to start at zero.
+ */
+#define FD_STATIC_SCRATCH_BYTES ((size_t)44 << 20)
+FD_API fd_status fd_verify_draft_attn_static(const fd_attn_args *args, void *hip_stream);
+
+/*
  * Greedy lossless acceptance (Sec. 3, temperature -> 0).
  *
  * target_logits  device [total_rows][row_stride] of dtype dt; only the first

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <atomic>
 
 namespace fd {
 hipError_t run_attn_generic(const AttnParams& p, int dtype, hipStream_t st);
@@ -37,6 +38,9 @@ hipError_t run_accept_sample(const void* target, const void* draft, int dt, long
 }  // namespace fd
 
 namespace {
+
+// FD_STATIC_SCRATCH_BYTES (flexdraft.h) covers the MFMA kernel's workspace at 128 tile rows per
+// work-group on up to 304 compute units (35.7 MB at 256).
 
 thread_local char g_err[512] = "";
 
@@ -122,6 +126,30 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
   return FD_OK;
 }
 
+
+// ---- static scratch of fd_verify_draft_attn_static ---------------------------------------------
+// The array lives in device memory of every GPU the library's code object is loaded on, from then
+// until the process ends.  On the host its name is only a handle: the device address is asked for
+// once per device (with that device current) and kept; only that address is ever handed to kernels.
+__device__ __align__(256) unsigned char scratch[FD_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+fd_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES)
+    return fail(FD_ERR_HIP, "hipGetDevice failed or device index %d not below %d", dev, MAX_DEVICES);
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(FD_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);       // every thread would store the same address
+  }
+  *out = ptr;
+  return FD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -135,7 +163,8 @@ size_t fd_verify_draft_attn_workspace(const fd_attn_args* a) {
   return plan.total_bytes;
 }
 
-fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
+// The attention call on the given workspace (the caller's, or the library's static scratch).
+static fd_status attn_call(const fd_attn_args* a, void* workspace, size_t workspace_bytes, void* hip_stream) {
   AttnPlan plan;
   fd_status st = plan_attn(a, &plan);
   if (st != FD_OK) return st;
@@ -153,10 +182,10 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   if (plan.use_mfma && (a->cache_stride_page >= (1ll << 31) || a->cache_stride_head >= (1ll << 31) ||
                         (long long)a->page_size * a->cache_stride_token >= (1ll << 31)))
     return fail(FD_ERR_UNSUPPORTED, "cache strides of 2^31 elements or more");
-  if (!a->workspace) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
-  if (a->workspace_bytes < plan.total_bytes)
-    return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", a->workspace_bytes, plan.total_bytes);
-  if (reinterpret_cast<uintptr_t>(a->workspace) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  if (!workspace) return fail(FD_ERR_INVALID_ARG, "workspace is NULL");
+  if (workspace_bytes < plan.total_bytes)
+    return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", workspace_bytes, plan.total_bytes);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
   if (!aligned16(a->q) || !aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->out) ||
       !aligned16(a->k_cache) || !aligned16(a->v_cache))
     return fail(FD_ERR_INVALID_ARG, "q, k_new, v_new, out, k_cache and v_cache must be 16-byte aligned");
@@ -173,18 +202,37 @@ fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   p.row_indptr = a->row_indptr; p.verify_len = a->verify_len; p.mask_vis = a->mask_vis;
   p.mask_blocks = a->mask_blocks;
   p.q = a->q; p.k_new = a->k_new; p.v_new = a->v_new; p.out = a->out; p.lse = a->lse;
-  p.part_acc = reinterpret_cast<float*>(a->workspace);
-  p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a->workspace) + plan.acc_bytes);
+  p.part_acc = reinterpret_cast<float*>(workspace);
+  p.part_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan.acc_bytes);
   p.status = a->status;
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, a->workspace, a->kv_chunk, stream)
+  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, workspace, a->kv_chunk, stream)
                                : fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
-  e = plan.use_mfma ? fd::run_attn_mfma_combine(p, a->workspace, stream)
+  e = plan.use_mfma ? fd::run_attn_mfma_combine(p, workspace, stream)
                     : fd::run_attn_combine(p, a->dtype, 0, 0, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
   return FD_OK;
+}
+
+fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
+  if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
+  return attn_call(a, a->workspace, a->workspace_bytes, hip_stream);
+}
+
+fd_status fd_verify_draft_attn_static(const fd_attn_args* a, void* hip_stream) {
+  if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
+  AttnPlan plan;
+  fd_status st = plan_attn(a, &plan);
+  if (st != FD_OK) return st;
+  if (plan.total_bytes > FD_STATIC_SCRATCH_BYTES)
+    return fail(FD_ERR_WORKSPACE_TOO_SMALL, "this call needs %zu bytes of scratch, the static buffer holds %zu: use "
+                "fd_verify_draft_attn with a workspace of your own", plan.total_bytes, (size_t)FD_STATIC_SCRATCH_BYTES);
+  void* ptr = nullptr;
+  st = static_scratch(&ptr);
+  if (st != FD_OK) return st;
+  return attn_call(a, ptr, FD_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling) {

@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflexdraft.so")
+# FLEXDRAFT_LIB names another build of the same library (same C ABI), e.g. one compiled with other tuning macros
+LIB_PATH = os.environ.get("FLEXDRAFT_LIB") or os.path.join(_HERE, "libflexdraft.so")
 
 FD_F32, FD_BF16 = 0, 1
 FD_ATTN_FORCE_GENERIC = 1
@@ -50,7 +51,7 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_version"]
+           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_version", "fd_verify_draft_attn_static"]
 
 
 def load() -> C.CDLL:
@@ -85,6 +86,8 @@ def load() -> C.CDLL:
     lib.fd_draft_select_workspace.argtypes = [C.c_int32, C.c_int32]
     lib.fd_append_kv.restype = C.c_int
     lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fd_verify_draft_attn_static.restype = C.c_int
+    lib.fd_verify_draft_attn_static.argtypes = [C.POINTER(fd_attn_args), C.c_void_p]
     lib.fd_select_branch.restype = C.c_int
     lib.fd_select_branch.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 3 + [C.c_void_p] * 3
     lib.fd_last_error.restype = C.c_char_p
@@ -164,6 +167,14 @@ def fd_verify_draft_attn_workspace(args: fd_attn_args) -> int:
 def fd_verify_draft_attn(args: fd_attn_args, stream=None) -> None:
     """Enqueue the attention call described by `args` on `stream` (default: torch's current stream)."""
     _check(load().fd_verify_draft_attn(C.byref(args), _stream(stream)))
+
+
+def fd_verify_draft_attn_static(args: fd_attn_args, stream=None) -> None:
+    """The same call on the library's own static scratch buffer: args.workspace is ignored."""
+    _check(load().fd_verify_draft_attn_static(C.byref(args), _stream(stream)))
+
+
+FD_STATIC_SCRATCH_BYTES = 44 << 20
 
 
 def fd_accept_workspace(batch: int, total_rows: int, vocab: int, sampling: bool) -> int:
