@@ -781,21 +781,26 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
     for (int e = 0; e < 4; ++e) num[e] = fmaf(wa, x[e], num[e]);
     den = fmaf(wgt, ml[1], den);
   };
-  if (np <= 4) {
-    // the usual case: everything is requested at once, one memory latency
-    f32x4 ml[4]; u32x2 a[4];
+  // up to 24 pieces: everything is requested at once (one memory latency), then reduced
+  auto merge_at_once = [&](auto n_c) {
+    constexpr int N = decltype(n_c)::value;
+    f32x4 ml[N]; u32x2 a[N];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < N; ++u) {
       const int pu = min(u, np - 1);
       ml[u] = *ml_of(pu); a[u] = *acc_of(pu);
       if (u >= np) ml[u][0] = -INFINITY;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) M = fmaxf(M, ml[u][0]);
+    for (int u = 0; u < N; ++u) M = fmaxf(M, ml[u][0]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) add_piece(ml[u], a[u]);
-  } else {
-    // many pieces (a long item spread over many work-groups): eight at a time, all of a batch
+    for (int u = 0; u < N; ++u) add_piece(ml[u], a[u]);
+  };
+  if (np <= 4) merge_at_once(std::integral_constant<int, 4>{});
+  else if (np <= 8) merge_at_once(std::integral_constant<int, 8>{});
+  else if (np <= 24) merge_at_once(std::integral_constant<int, 24>{});
+  else {
+    // a very long item spread over more work-groups than that: eight at a time, all of a batch
     // requested together, with a running maximum (the sums are rescaled when it grows)
     for (int p0 = 0; p0 < np; p0 += 8) {
       f32x4 ml[8]; u32x2 a[8];
