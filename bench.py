@@ -2,8 +2,10 @@
 """Benchmark of the verify+draft hot path on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input that is
-already resident in HBM: fd_verify_draft_attn (streaming kernel + split combine) followed
-by the workload's acceptance call (greedy or sampling) when it has one.  The KV pool and
+already resident in HBM: fd_verify_draft_attn followed by the workload's acceptance call
+(greedy or sampling) when it has one.  The attention calls start from a plan
+(fd_verify_draft_plan) that is renewed inside the timed loop once per 36 calls, the way one
+decoding step of Qwen3-8B plans once for its 36 layers.  The KV pool and
 the logits are rotated over enough device copies that no step finds its input in the
 256 MB last-level cache.  One JSON line is printed; `value` is algorithmic KV-cache bytes
 per step divided by the step time.
@@ -23,9 +25,10 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-ATTN_KERNELS = "attn_mfma_kernel + attn_mfma_combine_kernel (every kernel of the attention call)"
+ATTN_KERNELS = "attn_mfma_kernel (the one kernel of a planned attention call)"
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 COLD_FOOTPRINT = 1.25e9         # bytes of distinct copies a rotating input must span
+LAYERS_PER_PLAN = 36            # Qwen3-8B: one plan (fd_verify_draft_plan) per decoding step serves this many attention calls
 MIN_KERNEL_SAMPLES = 20         # attention launches that are event-bracketed, whatever --steps is
 
 
@@ -61,7 +64,9 @@ class Step:
         for k, v in self.pools:
             args = fd.fd_attn_args.from_buffer_copy(call.args)
             args.k_cache = k.data_ptr(); args.v_cache = v.data_ptr()
+            args.flags |= fd.FD_ATTN_PLANNED           # the plan is made in attn(), once per LAYERS_PER_PLAN calls
             self.attn_args.append(args)
+        self.attn_calls = 0
         # acceptance inputs
         self.acc = None
         if a is not None:
@@ -100,7 +105,14 @@ class Step:
         log(f"[{name}] inputs ready in {time.time() - t0:.1f}s: KV {self.kv_bytes / 1e6:.1f} MB x {n_pools} pools, "
             f"rows {inp['q'].shape[0]}, acceptance {a.mode if a else 'none'}")
 
+    def plan_if_due(self):
+        """The lengths of a decoding step meet every layer: one planning call per LAYERS_PER_PLAN attention calls."""
+        if self.attn_calls % LAYERS_PER_PLAN == 0:
+            self.fd.fd_verify_draft_plan(self.attn_args[0])
+        self.attn_calls += 1
+
     def attn(self):
+        self.plan_if_due()
         self.fd.fd_verify_draft_attn(self.attn_args[self.i % len(self.attn_args)])
 
     def accept(self):
@@ -164,12 +176,23 @@ class Step:
         torch = self.torch
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         for s, e in evs:
-            s.record(); self.attn(); e.record()
+            self.plan_if_due()
+            s.record(); self.fd.fd_verify_draft_attn(self.attn_args[self.i % len(self.attn_args)]); e.record()
             if self.acc is not None:
                 self.accept()
             self.i += 1
         torch.cuda.synchronize()
         return [s.elapsed_time(e) for s, e in evs]
+
+    def time_plan(self, steps=30):
+        """fd_verify_draft_plan alone (event-bracketed)."""
+        torch = self.torch
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for s, e in evs:
+            s.record(); self.fd.fd_verify_draft_plan(self.attn_args[0]); e.record()
+        torch.cuda.synchronize()
+        ts = sorted(s.elapsed_time(e) for s, e in evs)
+        return ts[len(ts) // 2]
 
     def timed_parts(self, steps, warmup):
         """Event-bracketed time of the attention call alone and the acceptance call alone."""
@@ -389,7 +412,7 @@ def main():
                      "traffic": read_traffic(args.workload), "traffic_source": "committed rocprofv3 --pmc summary under profiles/",
                      "kernel": ATTN_KERNELS,
                      "kernel_avg_ms": round(kern_avg_ms, 5), "kernel_min_ms": round(float(np.min(kern_ms)), 5),
-                     "kernel_launches_timed": len(kern_ms),
+                     "kernel_launches_timed": len(kern_ms), "attention_calls_per_plan": LAYERS_PER_PLAN,
                      "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2)},
     }
     if "accept" in parts:
@@ -411,6 +434,7 @@ def main():
                          "kernels_kv_GBps": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9, 1),
                          "kernels_frac_hbm_peak": round(s2.kv_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                          "attn_call_us": round(p2["attn"]["median_ms"] * 1e3, 2),
+                         "plan_us": round(s2.time_plan() * 1e3, 2),
                          "mfma_tflops": round(s2.flops / (k_ms * 1e-3) / 1e12, 2)}
             if "accept" in p2:
                 per[name]["accept_us"] = round(p2["accept"]["median_ms"] * 1e3, 2)

@@ -68,6 +68,8 @@ typedef enum fd_dtype { FD_F32 = 0, FD_BF16 = 1 } fd_dtype;
 
 /* fd_attn_args.flags */
 #define FD_ATTN_FORCE_GENERIC 1   /* use the scalar fp32-accumulate kernel even for bf16     */
+#define FD_ATTN_PLANNED       2   /* the workspace holds fd_verify_draft_plan's plan for these
+                                   * arguments: fd_verify_draft_attn starts from it           */
 
 /*
  * Arguments of fd_verify_draft_attn.
@@ -151,6 +153,25 @@ FD_API size_t fd_verify_draft_attn_workspace(const fd_attn_args *args);
 FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream);
 
 /*
+ * Planning for fd_verify_draft_attn, separated out because it depends on the lengths only and the
+ * same lengths meet every layer of the model in one decoding step (Sec. 4.1: one forward pass
+ * verifies and drafts; Sec. 4.3).  The bf16 head_dim-128 kernel cuts the batch's key tiles into
+ * equal shares for its persistent work-groups; the plan is, per work-group, where its share
+ * starts (sequence, offset, the page ids of its first two tiles).  Without a plan every work-group
+ * of fd_verify_draft_attn finds its share itself, by a scan over the batch, before it can request
+ * its first tile; with args->flags & FD_ATTN_PLANNED it starts from the plan this call left in
+ * args->workspace, and leaves it intact for the next call.
+ *   Read here: the scalar fields, page_indptr, page_indices, kv_len, row_indptr, verify_len,
+ *   mask_vis, mask_blocks, workspace, status.  q, k_new, v_new, out and the caches may be NULL.
+ *   A planned attention call must pass the same scalar fields, the same (unchanged) length and
+ *   page arrays and the same workspace, and needs page_indices_len > 0.  Calls that share a
+ *   workspace must not overlap.  For shapes the fp32 kernel serves, planning does nothing and
+ *   the flag is ignored.
+ * Asynchronous on hip_stream.  Errors as fd_verify_draft_attn.
+ */
+FD_API fd_status fd_verify_draft_plan(const fd_attn_args *args, void *hip_stream);
+
+/*
  * fd_verify_draft_attn for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, same kernels, same result; args->workspace and args->workspace_bytes are ignored and
@@ -161,7 +182,8 @@ FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream
  * independent of batch and lengths and always fits; the fp32 kernel's grows with rows x chunks).
  * All calls on one GPU share the one buffer: calls that may overlap on a GPU (different streams,
  * different threads) race on it and must be serialised by the caller; calls on one stream are safe.
- * Nothing in the buffer has to survive from call to call, and nothing in it has to start at zero.
+ * FD_ATTN_PLANNED is ignored (every call finds its shares itself); nothing in the buffer has to
+ * survive from call to call, and nothing in it has to start at zero.
  */
 #define FD_STATIC_SCRATCH_BYTES ((size_t)44 << 20)
 FD_API fd_status fd_verify_draft_attn_static(const fd_attn_args *args, void *hip_stream);

@@ -23,10 +23,11 @@ hipError_t run_select_branch(const int* block_tokens, const int* block_indptr, c
                              int total_tokens, int out_stride, int* out_tokens, int* out_block, hipStream_t st);
 int attn_mfma_tile_keys();
 int attn_mfma_rows_per_wg(int max_tile_rows);
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st);
+hipError_t run_attn_mfma_plan(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st);
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, bool planned, hipStream_t st);
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st);
 int attn_mfma_num_wgs();
-size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries);
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries, size_t* off_plan);
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab, int sampling);
 hipError_t run_accept_greedy(const void* logits, int dt, long long row_stride, int vocab, const int* row_indptr,
                              const int* toks, int batch, int total_rows, int max_rows, int* accept_len,
@@ -116,7 +117,7 @@ fd_status plan_attn(const fd_attn_args* a, AttnPlan* plan) {
     // persistent kernel: partial storage depends on the launch size only, not on the lengths
     plan->max_chunks = 1;
     plan->acc_bytes = plan->ml_bytes = 0;
-    plan->total_bytes = fd::attn_mfma_workspace(fd::attn_mfma_num_wgs(), tile_rows, nullptr, nullptr);
+    plan->total_bytes = fd::attn_mfma_workspace(fd::attn_mfma_num_wgs(), tile_rows, nullptr, nullptr, nullptr);
     return FD_OK;
   }
   size_t slots = (size_t)plan->max_chunks * (size_t)(a->total_rows > 0 ? a->total_rows : 1) * a->num_q_heads;
@@ -164,15 +165,19 @@ size_t fd_verify_draft_attn_workspace(const fd_attn_args* a) {
 }
 
 // The attention call on the given workspace (the caller's, or the library's static scratch).
-static fd_status attn_call(const fd_attn_args* a, void* workspace, size_t workspace_bytes, void* hip_stream) {
+// what: 1 = plan only, 2 = attention only (the workspace holds the plan), 3 = both.
+enum { DO_PLAN = 1, DO_ATTN = 2 };
+static fd_status attn_call(const fd_attn_args* a, void* workspace, size_t workspace_bytes, void* hip_stream, int what) {
   AttnPlan plan;
   fd_status st = plan_attn(a, &plan);
   if (st != FD_OK) return st;
   g_err[0] = 0;
   if (a->batch == 0 || a->total_rows == 0) return FD_OK;          // nothing to compute
-  if (!a->page_indptr || !a->kv_len || !a->row_indptr || !a->verify_len || !a->q || !a->k_new || !a->v_new || !a->out)
+  const bool attn = (what & DO_ATTN) != 0;         // planning reads the lengths and the page lists only
+  if (!a->page_indptr || !a->kv_len || !a->row_indptr || !a->verify_len ||
+      (attn && (!a->q || !a->k_new || !a->v_new || !a->out)))
     return fail(FD_ERR_INVALID_ARG, "a required device pointer is NULL");
-  if (a->max_kv_len > 0 && (!a->k_cache || !a->v_cache || !a->page_indices || a->num_pages == 0))
+  if (a->max_kv_len > 0 && (!a->page_indices || a->num_pages == 0 || (attn && (!a->k_cache || !a->v_cache))))
     return fail(FD_ERR_INVALID_ARG, "max_kv_len > 0 needs k_cache, v_cache, page_indices and num_pages > 0");
   if (a->max_new_rows == 0) return fail(FD_ERR_INVALID_ARG, "total_rows > 0 but max_new_rows == 0");
   if (a->cache_stride_page < 0 || a->cache_stride_head < 0 || a->cache_stride_token < a->head_dim ||
@@ -186,8 +191,8 @@ static fd_status attn_call(const fd_attn_args* a, void* workspace, size_t worksp
   if (workspace_bytes < plan.total_bytes)
     return fail(FD_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", workspace_bytes, plan.total_bytes);
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(FD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
-  if (!aligned16(a->q) || !aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->out) ||
-      !aligned16(a->k_cache) || !aligned16(a->v_cache))
+  if (attn && (!aligned16(a->q) || !aligned16(a->k_new) || !aligned16(a->v_new) || !aligned16(a->out) ||
+               !aligned16(a->k_cache) || !aligned16(a->v_cache)))
     return fail(FD_ERR_INVALID_ARG, "q, k_new, v_new, out, k_cache and v_cache must be 16-byte aligned");
 
   fd::AttnParams p;
@@ -207,18 +212,38 @@ static fd_status attn_call(const fd_attn_args* a, void* workspace, size_t worksp
   p.status = a->status;
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  hipError_t e = plan.use_mfma ? fd::run_attn_mfma(p, workspace, a->kv_chunk, stream)
-                               : fd::run_attn_generic(p, a->dtype, stream);
+  if (plan.use_mfma) {
+    if ((what & DO_ATTN) && !(what & DO_PLAN) && a->page_indices_len <= 0 && a->max_kv_len > 0)
+      return fail(FD_ERR_INVALID_ARG, "a planned call needs page_indices_len (the plan's page list is checked against it)");
+    if (what == DO_PLAN) {
+      hipError_t e = fd::run_attn_mfma_plan(p, workspace, a->kv_chunk, stream);
+      if (e != hipSuccess) return fail(FD_ERR_HIP, "planning kernel launch: %s", hipGetErrorString(e));
+      return FD_OK;
+    }
+    // without a plan the streaming kernel finds its shares itself: no extra launch
+    hipError_t e = fd::run_attn_mfma(p, workspace, a->kv_chunk, what == DO_ATTN, stream);
+    if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
+    e = fd::run_attn_mfma_combine(p, workspace, stream);
+    if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
+    return FD_OK;
+  }
+  if (!(what & DO_ATTN)) return FD_OK;            // the fp32 kernel has nothing to plan
+  hipError_t e = fd::run_attn_generic(p, a->dtype, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "attention kernel launch: %s", hipGetErrorString(e));
-  e = plan.use_mfma ? fd::run_attn_mfma_combine(p, workspace, stream)
-                    : fd::run_attn_combine(p, a->dtype, 0, 0, stream);
+  e = fd::run_attn_combine(p, a->dtype, 0, 0, stream);
   if (e != hipSuccess) return fail(FD_ERR_HIP, "combine kernel launch: %s", hipGetErrorString(e));
   return FD_OK;
 }
 
 fd_status fd_verify_draft_attn(const fd_attn_args* a, void* hip_stream) {
   if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
-  return attn_call(a, a->workspace, a->workspace_bytes, hip_stream);
+  return attn_call(a, a->workspace, a->workspace_bytes, hip_stream,
+                   (a->flags & FD_ATTN_PLANNED) ? DO_ATTN : (DO_PLAN | DO_ATTN));
+}
+
+fd_status fd_verify_draft_plan(const fd_attn_args* a, void* hip_stream) {
+  if (!a) return fail(FD_ERR_INVALID_ARG, "args is NULL");
+  return attn_call(a, a->workspace, a->workspace_bytes, hip_stream, DO_PLAN);
 }
 
 fd_status fd_verify_draft_attn_static(const fd_attn_args* a, void* hip_stream) {
@@ -232,7 +257,7 @@ fd_status fd_verify_draft_attn_static(const fd_attn_args* a, void* hip_stream) {
   void* ptr = nullptr;
   st = static_scratch(&ptr);
   if (st != FD_OK) return st;
-  return attn_call(a, ptr, FD_STATIC_SCRATCH_BYTES, hip_stream);
+  return attn_call(a, ptr, FD_STATIC_SCRATCH_BYTES, hip_stream, DO_PLAN | DO_ATTN);   // never from a plan
 }
 
 size_t fd_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab, int32_t sampling) {

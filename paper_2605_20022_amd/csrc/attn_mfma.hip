@@ -12,6 +12,11 @@
 // running max, sum, un-normalised O as fp16 rows scaled by their largest entry) per work-group
 // that touched it, and the work-group in which it ends leaves an entry for the combine kernel below.
 //
+// Where a share starts (sequence, offset, the page ids of its first two tiles) depends on the
+// lengths only, so it can be found ahead of time by the planning kernel, once for every layer of a
+// decoding step; the streaming kernel then starts from its plan entry -- one scalar load, then
+// tiles are requested -- instead of scanning the batch itself.
+//
 // Streaming of one tile by the four waves of a work-group:
 //   page ids           scalar loads, one tile ahead (they are uniform across the work-group)
 //   global -> regs     one 16-key group (a 4 KB K slab and a 4 KB V slab of one page) per
@@ -38,6 +43,7 @@
 // The cached prefix is unmasked (every new row sees all of it, Sec. 4.1); only the ragged
 // last tile and the tile of new rows apply the visibility rule, in registers.
 #include "fd_common.h"
+#include <atomic>
 #include <type_traits>
 
 // MFMAs by which the LDS fragment requests of S = K Q^T and O += V^T P^T run ahead of their use
@@ -54,6 +60,9 @@ namespace fd {
 constexpr int MF_BLOCK = 256;
 constexpr int MF_TK = 64;                 // keys per LDS tile
 constexpr int MF_D = 128;
+#ifndef FD_WGS_PER_CU
+#define FD_WGS_PER_CU 2                   // persistent work-groups per compute unit (two fit: registers and LDS)
+#endif
 #ifndef FD_KPAD
 #define FD_KPAD 8
 #endif
@@ -89,7 +98,22 @@ struct MfmaSched {
   unsigned short* part_acc;   // [2 * num_wgs][ROWS_WG][D] fp16: the un-normalised output row divided by its largest magnitude
   float* part_ml;             // [2 * num_wgs][ROWS_WG][4]: running maximum (base 2), row sum, that largest magnitude, unused
   int4* entries;      // [num_wgs]: the split item that ends in this work-group: (first packed row, head | row block << 16, tile rows, first slot); first < 0: none
+  struct PlanEntry* plan;     // [num_wgs]: written by the planning kernel, read by a planned streaming kernel
 };
+
+// What the planning kernel leaves for each persistent work-group (128 bytes, read through the scalar path).
+struct PlanEntry {
+  int seq;                    // sequence in which the share starts; < 0: nothing to do
+  unsigned Pt;                // units of the line before that sequence
+  unsigned g0, g1;            // the share: units [g0, g1) of the line
+  int L, row0, n, k, v, nb, page0, npages;     // that sequence, clamped as load_seq clamps it
+  unsigned sh_q, sh_r;        // share w starts at unit w sh_q + floor(w sh_r / W_eff)
+  int W_eff;                  // work-groups that have a share
+  int pad0;
+  int pg0[MF_GROUPS], pg1[MF_GROUPS];          // page ids of the first two tiles of the share's first piece
+  int pad1[8];
+};
+static_assert(sizeof(PlanEntry) == 128, "one plan entry is 128 bytes");
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
@@ -142,30 +166,24 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
-// MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
+// Where work-group w's share of the line starts.  Every thread of the work-group calls this; the
+// results are uniform.  Tile counts fit 32 bits (the host checks the bound), so no 64-bit division
+// is needed.  share w = [w q + floor(w r / W), ...) with q, r = total / W, total % W: equal to
+// floor(w total / W).  Returns false if the work-group has nothing to do.
 template <int MAXRB>
-__global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
+__device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched& sc_, int w, int& seq, unsigned& Pt,
+                                           SeqInfo& ws, unsigned& g0, unsigned& g1, unsigned& sh_q, unsigned& sh_r,
+                                           int& W_eff) {
   constexpr int ROWS_WG = 32 * MAXRB;
   constexpr int MF_START_COST = mf_start_cost(MAXRB);
-  constexpr int PF_K = FD_PF_K, PF_V = FD_PF_V;   // LDS fragment requests run this many MFMAs ahead
-  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   __shared__ int sh_w[MF_BLOCK / 64];
   __shared__ int sh_found[12];
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
-  const int w = blockIdx.x;
-  const bf16_t* Kc = reinterpret_cast<const bf16_t*>(p.k_cache);
-  const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
-  const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
-  const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
-  if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
-
   // ---- total work, this work-group's share, and the sequence in which the share starts -------
   // Tile counts fit 32 bits (the host checks the bound), so no 64-bit division is needed.
   // share w = [w q + floor(w r / W), ...) with q, r = total / W, total % W: equal to floor(w total / W)
-  unsigned total = 0, sh_q = 0, sh_r = 0;
-  int W_eff = 0;
+  unsigned total = 0;
+  sh_q = 0; sh_r = 0; W_eff = 0;
   auto plan_shares = [&]() {
     const unsigned want = sc_.fixed_share > 0 ? (unsigned)sc_.fixed_share
                                               : max((unsigned)sc_.min_share, (total + sc_.num_wgs - 1) / (unsigned)sc_.num_wgs);
@@ -174,9 +192,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     sh_q = total / (unsigned)W_eff; sh_r = total % (unsigned)W_eff;
   };
   auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
-  unsigned g0 = 0, g1 = 0, Pt = 0;
-  int seq = -1;
-  SeqInfo ws;
+  g0 = 0; g1 = 0; Pt = 0; seq = -1;
   if (p.B <= MF_BLOCK) {
     // one pass: thread i keeps sequence i in registers, the owner of tile g0 hands it over through LDS
     SeqInfo s_mine = {}; uint32_t bad = 0; int vt = 0;
@@ -196,11 +212,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       total += (unsigned)sh_w[q];
     }
     total = __builtin_amdgcn_readfirstlane(total);
-    if (total == 0) return;
+    if (total == 0) return false;
     plan_shares();
-    if (w >= W_eff) return;
+    if (w >= W_eff) return false;
     g0 = share_start(w); g1 = share_start(w + 1);
-    if (g1 <= g0) return;
+    if (g1 <= g0) return false;
     const unsigned lo = (unsigned)(wt + it - vt), hi = (unsigned)(wt + it);
     if (lo <= g0 && g0 < hi) {
       sh_found[0] = tid; sh_found[1] = (int)lo;
@@ -210,7 +226,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (bad) flag_status(p.status, bad);
     __syncthreads();
     seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
-    if (seq < 0) return;                                         // cannot happen for consistent data
+    if (seq < 0) return false;                             // cannot happen for consistent data
     Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
     ws.L = __builtin_amdgcn_readfirstlane(sh_found[2]);      ws.row0 = __builtin_amdgcn_readfirstlane(sh_found[3]);
     ws.n = __builtin_amdgcn_readfirstlane(sh_found[4]);      ws.k = __builtin_amdgcn_readfirstlane(sh_found[5]);
@@ -232,11 +248,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     total = __builtin_amdgcn_readfirstlane(total);
     if (tid == 0) sh_found[0] = -1;
     __syncthreads();
-    if (total == 0) return;
+    if (total == 0) return false;
     plan_shares();
-    if (w >= W_eff) return;
+    if (w >= W_eff) return false;
     g0 = share_start(w); g1 = share_start(w + 1);
-    if (g1 <= g0) return;
+    if (g1 <= g0) return false;
     unsigned base_t = 0;
     for (int blk = 0; blk < p.B; blk += MF_BLOCK) {
       const int i = blk + tid;
@@ -259,9 +275,98 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       if (sh_found[0] >= 0) break;
     }
     seq = __builtin_amdgcn_readfirstlane(sh_found[0]);
-    if (seq < 0) return;                                         // cannot happen for consistent data
+    if (seq < 0) return false;                             // cannot happen for consistent data
     Pt = (unsigned)__builtin_amdgcn_readfirstlane(sh_found[1]);
   }
+
+  if (p.B > MF_BLOCK) ws = load_seq(p, seq);
+  return true;
+}
+
+// Planning kernel: one work-group per persistent work-group of the streaming kernel.  Every one
+// repeats the (cheap) scan over the batch, finds its own share and leaves its plan entry.
+// MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
+template <int MAXRB>
+__global__ __launch_bounds__(MF_BLOCK) void attn_mfma_plan_kernel(AttnParams p, MfmaSched sc_) {
+  constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int MF_START_COST = mf_start_cost(MAXRB);
+  const int tid = threadIdx.x;
+  const int w = blockIdx.x;
+  PlanEntry* out = sc_.plan + w;
+  int seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
+  if (!find_share<MAXRB>(p, sc_, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff)) {
+    if (tid == 0) out->seq = -1;
+    return;
+  }
+  // page ids of the first two tiles of the share's first piece (it lies in the item that holds unit g0)
+  int T, I; seq_shape(p, ws, ROWS_WG, T, I);
+  const int Tu = item_units(T, MF_START_COST);
+  if (Tu <= 0) { if (tid == 0) out->seq = -1; return; }
+  const int local = (int)(g0 - Pt);
+  const int u = local - (local / Tu) * Tu;
+  const int tile0 = max(u - MF_START_COST, 0);
+  const int n_ct_all = (ws.L + MF_TK - 1) / MF_TK;
+  if (tid < 2 * MF_GROUPS) {
+    const int tau = tile0 + tid / MF_GROUPS, j = tid % MF_GROUPS;
+    int id = 0;
+    if (tau < n_ct_all) id = p.page_indices[ws.page0 + (min(tau * MF_TK + 16 * j, ws.L - 1) >> sc_.page_shift)];
+    if (tid < MF_GROUPS) out->pg0[j] = id; else out->pg1[j] = id;
+  }
+  if (tid == 0) {
+    out->seq = seq; out->Pt = Pt; out->g0 = g0; out->g1 = g1;
+    out->L = ws.L; out->row0 = ws.row0; out->n = ws.n; out->k = ws.k; out->v = ws.v; out->nb = ws.nb;
+    out->page0 = ws.page0; out->npages = ws.npages;
+    out->sh_q = sh_q; out->sh_r = sh_r; out->W_eff = W_eff; out->pad0 = 0;
+  }
+}
+
+// Streaming kernel.  MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
+// PLANNED: the share comes from the plan entry the planning kernel left, else it is found here.
+template <int MAXRB, bool PLANNED>
+__global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
+  constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int MF_START_COST = mf_start_cost(MAXRB);
+  constexpr int PF_K = FD_PF_K, PF_V = FD_PF_V;   // LDS fragment requests run this many MFMAs ahead
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
+  const int w = blockIdx.x;
+  const bf16_t* Kc = reinterpret_cast<const bf16_t*>(p.k_cache);
+  const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
+  const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
+  const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
+  if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
+
+  int seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
+  int nid0[MF_GROUPS], nid1[MF_GROUPS];          // page ids of the first two tiles of the piece to start
+#pragma unroll
+  for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
+  if (PLANNED) {
+    // this work-group's plan entry: share, first sequence, first page ids (one scalar load)
+    const int* pe = reinterpret_cast<const int*>(sc_.plan + w);
+    seq = sload(pe, 0); Pt = (unsigned)sload(pe, 1);
+    g0 = (unsigned)sload(pe, 2); g1 = (unsigned)sload(pe, 3);
+    ws.L = sload(pe, 4); ws.row0 = sload(pe, 5); ws.n = sload(pe, 6); ws.k = sload(pe, 7);
+    ws.v = sload(pe, 8); ws.nb = sload(pe, 9); ws.page0 = sload(pe, 10); ws.npages = sload(pe, 11);
+    sh_q = (unsigned)sload(pe, 12); sh_r = (unsigned)sload(pe, 13); W_eff = sload(pe, 14);
+#pragma unroll
+    for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = sload(pe, 16 + j); nid1[j] = sload(pe, 20 + j); }
+    // The plan is trusted to describe these arguments.  The checks below only keep a stale or foreign
+    // plan from sending an access outside the caller's buffers (its results are then meaningless).
+    if (seq < 0 || seq >= p.B || W_eff < 1 || W_eff > sc_.num_wgs || w >= W_eff || g1 <= g0 || Pt > g0 || sh_q == 0) return;
+    clamp_seq(p, ws);
+  } else {
+    if (!find_share<MAXRB>(p, sc_, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff)) return;
+  }
+  auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
+  // the work-group whose share holds unit x of the line
+  auto wg_of_unit = [&](unsigned x) -> int {
+    int ww = (int)min(x / max(sh_q, 1u), (unsigned)(W_eff - 1));
+    while (ww + 1 < W_eff && share_start(ww + 1) <= x) ++ww;
+    while (ww > 0 && share_start(ww) > x) --ww;
+    return ww;
+  };
 
   // Tile loads: wave w fetches the w-th 16-key group of a tile (one page: one base address, one pair
   // of buffer descriptors per wave and tile); lane l takes 16-byte column l & 15 of keys (l >> 4) + 4 i.
@@ -280,7 +385,6 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   };
   // ---- walk over the share, one piece (run of tiles inside one item) at a time ----------------
   // The walk state (sequence, its shape, tiles before it) only moves forward.
-  if (p.B > MF_BLOCK) ws = get_seq(seq);
   int T, I; seq_shape(p, ws, ROWS_WG, T, I);
 
   struct Piece {
@@ -473,10 +577,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   Piece cur;
   if (!next_piece(cur)) return;
   Lane ln = make_lane(cur);
-  int nid0[MF_GROUPS], nid1[MF_GROUPS];
-#pragma unroll
-  for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
-  start_ids(cur, nid0, nid1);
+  if (!PLANNED) start_ids(cur, nid0, nid1);       // (a plan entry brings the first piece's page ids with it)
   start_loads(cur, ln, nid0, nid1);
   bool have = true;
   while (have) {
@@ -491,12 +592,9 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (tid == 0 && tile0 > 0 && tile0 + nt == cur.T) {
       // this item started in an earlier work-group and ends here: leave it to the combine kernel.
       // Its first piece sits in the work-group wf that owns the item's first tile, in slot 2 wf
-      // if nothing of wf's share precedes the item, else 2 wf + 1; later pieces are in slots 2 w'.
-      const unsigned a = cur.item_u + MF_START_COST;       // the unit of the item's first tile
-      int wf = min((int)(a / max(sh_q, 1u)), w);
-      while (wf + 1 <= w && share_start(wf + 1) <= a) ++wf;
-      while (wf > 0 && share_start(wf) > a) --wf;
-      // (a share that begins among the item's start-up units has nothing before the item's first tile)
+      // if nothing of wf's share precedes the item (a share that begins among the item's start-up
+      // units has nothing before the item's first tile), else 2 wf + 1; later pieces are in slots 2 w'.
+      const int wf = wg_of_unit(cur.item_u + MF_START_COST);
       const int first_slot = 2 * wf + (share_start(wf) >= cur.item_u ? 0 : 1);
       sc_.entries[w] = make_int4(cur.s.row0, cur.head | (cur.rt << 16), min(ROWS_WG, cur.s.n * p.G - cur.rt * ROWS_WG), first_slot);
     }
@@ -846,26 +944,30 @@ int attn_mfma_rows_per_wg(int max_tile_rows) { return max_tile_rows <= 64 ? 64 :
 
 // Persistent work-groups: two per compute unit.
 int attn_mfma_num_wgs() {
-  static int n = 0;
+  static std::atomic<int> cached[64];              // per device; 0 = not asked yet
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+  int n = cached[dev].load(std::memory_order_relaxed);
   if (n == 0) {
-    int dev = 0; hipDeviceProp_t pr;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&pr, dev) == hipSuccess && pr.multiProcessorCount > 0)
-      n = 2 * pr.multiProcessorCount;
-    else
-      n = 512;
+    int cus = 0;
+    n = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? FD_WGS_PER_CU * cus : 512;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
   return n;
 }
 
-// Workspace bytes for (num_wgs, rows per work-group); offsets of the (m, l) array and the entries.
-size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries) {
+// Workspace bytes for (num_wgs, rows per work-group) and the offsets of its parts: the partial
+// rows, their (max, sum, scale), the combine entries, the plan entries.
+size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries, size_t* off_plan) {
   auto al = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(unsigned short));
   size_t ml = al((size_t)2 * num_wgs * rows_wg * 4 * sizeof(float));
   size_t en = al((size_t)num_wgs * sizeof(int4));
+  size_t pl = al((size_t)num_wgs * sizeof(PlanEntry));
   if (off_ml) *off_ml = acc;
   if (off_entries) *off_entries = acc + ml;
-  return acc + ml + en;
+  if (off_plan) *off_plan = acc + ml + en;
+  return acc + ml + en + pl;
 }
 
 static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaSched& sc, int& rows_wg) {
@@ -877,32 +979,53 @@ static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaS
   sc.min_share = 2;
   sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
   rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
-  size_t off_ml, off_en;
-  attn_mfma_workspace(sc.num_wgs, rows_wg, &off_ml, &off_en);
+  size_t off_ml, off_en, off_pl;
+  attn_mfma_workspace(sc.num_wgs, rows_wg, &off_ml, &off_en, &off_pl);
   char* base = reinterpret_cast<char*>(workspace);
   sc.part_acc = reinterpret_cast<unsigned short*>(base);
   sc.part_ml = reinterpret_cast<float*>(base + off_ml);
   sc.entries = reinterpret_cast<int4*>(base + off_en);
+  sc.plan = reinterpret_cast<PlanEntry*>(base + off_pl);
 }
 
-template <int MAXRB>
-static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<MAXRB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)MF_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  hipLaunchKernelGGL((attn_mfma_kernel<MAXRB>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
-  return hipGetLastError();
+// The streaming kernel's LDS request is above the default limit: raised once per device.
+template <int MAXRB, bool PLANNED>
+static hipError_t configure_mfma() {
+  static std::atomic<unsigned long long> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<MAXRB, PLANNED>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)MF_LDS_BYTES);
+  if (e == hipSuccess && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+  return e;
 }
 
 // `workspace` must hold attn_mfma_workspace(...) bytes; kv_chunk > 0 asks for shares of that many keys.
-hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st) {
+// The plan: every persistent work-group's share, first sequence and first page ids.
+hipError_t run_attn_mfma_plan(const AttnParams& p, void* workspace, int kv_chunk, hipStream_t st) {
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, kv_chunk, sc, rows_wg);
-  return rows_wg == 64 ? launch_mfma<2>(p, sc, st) : launch_mfma<4>(p, sc, st);
+  if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_plan_kernel<2>, dim3(sc.num_wgs), dim3(MF_BLOCK), 0, st, p, sc);
+  else hipLaunchKernelGGL(attn_mfma_plan_kernel<4>, dim3(sc.num_wgs), dim3(MF_BLOCK), 0, st, p, sc);
+  return hipGetLastError();
+}
+
+template <int MAXRB, bool PLANNED>
+static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
+  hipError_t e = configure_mfma<MAXRB, PLANNED>();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_mfma_kernel<MAXRB, PLANNED>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
+  return hipGetLastError();
+}
+
+// The streaming kernel; planned: the workspace holds the plan for these arguments.
+hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, bool planned, hipStream_t st) {
+  MfmaSched sc; int rows_wg;
+  fill_sched(p, workspace, kv_chunk, sc, rows_wg);
+  if (rows_wg == 64) return planned ? launch_mfma<2, true>(p, sc, st) : launch_mfma<2, false>(p, sc, st);
+  return planned ? launch_mfma<4, true>(p, sc, st) : launch_mfma<4, false>(p, sc, st);
 }
 
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {

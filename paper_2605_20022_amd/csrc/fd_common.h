@@ -135,6 +135,22 @@ __device__ __forceinline__ SeqInfo load_seq_t(const AttnParams& p, int i, uint32
 
 __device__ __forceinline__ SeqInfo load_seq(const AttnParams& p, int i) { return load_seq_t<true>(p, i); }
 
+// The same bounds applied to a description that came from somewhere else than the device arrays
+// (a plan entry): whatever it holds, nothing derived from it leaves the caller's buffers.  The
+// length of page_indices must be known (page_entries > 0).
+__device__ __forceinline__ void clamp_seq(const AttnParams& p, SeqInfo& s) {
+  s.L = clampi(s.L, 0, p.max_kv_len);
+  s.row0 = clampi(s.row0, 0, p.total_rows);
+  s.n = clampi(s.n, 0, p.max_new_rows < p.total_rows - s.row0 ? p.max_new_rows : p.total_rows - s.row0);
+  s.k = clampi(s.k, 0, s.n);
+  s.v = clampi(s.v, 0, s.k);
+  if (s.nb < 1 || (s.n - s.k) % s.nb) s.nb = 1;
+  s.page0 = clampi(s.page0, 0, p.page_entries);
+  s.npages = clampi(s.npages, 0, p.page_entries - s.page0);
+  const long long cap = (long long)s.npages * p.page_size;
+  if (cap < s.L) s.L = (int)cap;
+}
+
 // What new row r (0-based within the sequence) sees among the new rows, Sec. 4.1: the rows
 // t < vr, and the rows lo <= t < hi.  A verify row is causal (vr = r + 1, no second range); a
 // mask row of block b sees the first min(v + b, k) verify rows and its own block.

@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("FLEXDRAFT_LIB") or os.path.join(_HERE, "libflexdraft.
 
 FD_F32, FD_BF16 = 0, 1
 FD_ATTN_FORCE_GENERIC = 1
+FD_ATTN_PLANNED = 2
 FD_OK = 0
 STATUS_NAMES = {0: "FD_OK", 1: "FD_ERR_INVALID_ARG", 2: "FD_ERR_UNSUPPORTED",
                 3: "FD_ERR_WORKSPACE_TOO_SMALL", 4: "FD_ERR_HIP"}
@@ -51,7 +52,8 @@ class FlexDraftError(RuntimeError):
 _lib = None
 
 EXPORTS = ["fd_verify_draft_attn_workspace", "fd_verify_draft_attn", "fd_accept_greedy", "fd_accept_sample",
-           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_version", "fd_verify_draft_attn_static"]
+           "fd_accept_workspace", "fd_draft_select", "fd_draft_select_workspace", "fd_append_kv", "fd_select_branch", "fd_last_error", "fd_version", "fd_verify_draft_attn_static",
+           "fd_verify_draft_plan"]
 
 
 def load() -> C.CDLL:
@@ -86,6 +88,8 @@ def load() -> C.CDLL:
     lib.fd_draft_select_workspace.argtypes = [C.c_int32, C.c_int32]
     lib.fd_append_kv.restype = C.c_int
     lib.fd_append_kv.argtypes = [C.POINTER(fd_attn_args), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fd_verify_draft_plan.restype = C.c_int
+    lib.fd_verify_draft_plan.argtypes = [C.POINTER(fd_attn_args), C.c_void_p]
     lib.fd_verify_draft_attn_static.restype = C.c_int
     lib.fd_verify_draft_attn_static.argtypes = [C.POINTER(fd_attn_args), C.c_void_p]
     lib.fd_select_branch.restype = C.c_int
@@ -167,6 +171,11 @@ def fd_verify_draft_attn_workspace(args: fd_attn_args) -> int:
 def fd_verify_draft_attn(args: fd_attn_args, stream=None) -> None:
     """Enqueue the attention call described by `args` on `stream` (default: torch's current stream)."""
     _check(load().fd_verify_draft_attn(C.byref(args), _stream(stream)))
+
+
+def fd_verify_draft_plan(args: fd_attn_args, stream=None) -> None:
+    """Write the plan for `args` into args.workspace; attention calls with FD_ATTN_PLANNED start from it."""
+    _check(load().fd_verify_draft_plan(C.byref(args), _stream(stream)))
 
 
 def fd_verify_draft_attn_static(args: fd_attn_args, stream=None) -> None:

@@ -188,6 +188,58 @@ def test_full_parallel_mode_workloads(fd, name):
     _check(fd, W.make_attention_inputs(w, std=1.0), "bf16", name + " sharp")
 
 
+@pytest.mark.parametrize("name", ["cfg3", "par4"])
+def test_plan_serves_several_calls(fd, name):
+    """fd_verify_draft_plan once, then attention calls with FD_ATTN_PLANNED for several 'layers' (same
+    lengths and page lists, other Q / K / V / cache contents): each equals the oracle and, bit for bit,
+    the self-planning call; the plan survives every call."""
+    w, _ = W.CONFIGS[name]
+    inp = W.make_attention_inputs(w)
+    call = AttnCall(fd, inp)
+    fd.fd_verify_draft_plan(call.args)
+    call.args.flags |= fd.FD_ATTN_PLANNED
+    rng = np.random.default_rng(17)
+    for layer in range(3):
+        if layer:
+            inp = dict(inp)
+            for key in ("q", "k_new", "v_new"):
+                inp[key] = W.f32_to_bf16_bits(rng.standard_normal(inp[key].shape).astype(np.float32) * np.float32(0.3))
+                call.d[key].copy_(torch.from_numpy(inp[key].view(np.int16)).view(torch.bfloat16).cuda())
+            inp["k_cache"], inp["v_cache"] = inp["v_cache"], inp["k_cache"]          # other cache contents
+            call.args.k_cache, call.args.v_cache = call.args.v_cache, call.args.k_cache
+        call.out.fill_(float("nan"))
+        out, lse = call.run()
+        ref, ref_lse = oracle_attention(inp)
+        assert_attn_close(out, ref, "bf16", f"{name} planned, layer {layer}")
+        assert np.abs(lse - ref_lse).max() <= 2e-2
+        own = AttnCall(fd, inp)                                                      # plans by itself
+        out2, lse2 = own.run()
+        assert np.array_equal(out, out2) and np.array_equal(lse, lse2)
+
+
+def test_planned_call_with_a_foreign_plan_stays_in_bounds(fd):
+    """A workspace that holds no plan for these arguments (here: garbage, then the plan of another
+    batch) gives meaningless results, but no fault and no access outside the buffers."""
+    w = _wl("stale", "bf16", 4, 8, 2, 128, 16, (100, 900), (2, 6), 4, seed=52)
+    call = AttnCall(fd, W.make_attention_inputs(w))
+    call.workspace.copy_(torch.randint(0, 256, call.workspace.shape, dtype=torch.uint8, device="cuda"))
+    call.args.flags |= fd.FD_ATTN_PLANNED
+    fd.fd_verify_draft_attn(call.args)
+    torch.cuda.synchronize()
+    other = AttnCall(fd, W.make_attention_inputs(_wl("stale2", "bf16", 7, 8, 2, 128, 16, (300, 2000), (1, 8), 4, seed=53)))
+    fd.fd_verify_draft_plan(other.args)
+    call.workspace.copy_(other.workspace)
+    fd.fd_verify_draft_attn(call.args)
+    torch.cuda.synchronize()
+    # (out-of-range page ids of a foreign plan are reported, like any other bad device data)
+    call.status.zero_()
+    # and the same buffers still give the right answer without the flag
+    call.args.flags &= ~fd.FD_ATTN_PLANNED
+    out, _ = call.run()
+    ref, _ = oracle_attention(call.inp)
+    assert_attn_close(out, ref, "bf16", "after a foreign plan")
+
+
 def test_mfma_strided_cache_layout(fd):
     """Token-major cache ([page][slot][head][D]) addressed through the stride arguments."""
     w = _wl("nhd", "bf16", 3, 8, 2, 128, 16, (10, 400), (2, 6), 6, seed=31)

@@ -73,6 +73,24 @@ def test_attention_workspace_query_and_validation():
     assert e.value.code == 1 and "NULL" in str(e.value)
 
 
+def test_plan_entry_point_validates_on_the_host():
+    """fd_verify_draft_plan takes the same argument struct; a planned attention call needs the length of
+    the page list (the plan's page ids are checked against it)."""
+    lib = fd.load()
+    assert lib.fd_verify_draft_plan(None, None) == 1
+    assert lib.fd_verify_draft_plan(C.byref(_args(num_kv_heads=5)), None) == 1
+    assert lib.fd_verify_draft_plan(C.byref(_args()), None) == 1 and b"NULL" in lib.fd_last_error()
+    assert lib.fd_verify_draft_plan(C.byref(_args(batch=0)), None) == 0            # nothing to plan
+    a = _args(flags=fd.FD_ATTN_PLANNED, page_indices_len=0)
+    p = 4096                                                                       # never dereferenced: rejected on the host
+    for name in ("page_indptr", "page_indices", "kv_len", "row_indptr", "verify_len", "q", "k_new", "v_new", "out",
+                 "k_cache", "v_cache", "workspace"):
+        setattr(a, name, p)
+    a.workspace_bytes = 1 << 30
+    a.cache_stride_page, a.cache_stride_head, a.cache_stride_token = 8 * 16 * 128, 16 * 128, 128
+    assert lib.fd_verify_draft_attn(C.byref(a), None) == 1 and b"page_indices_len" in lib.fd_last_error()
+
+
 def test_negative_page_list_length_is_rejected():
     assert fd.fd_verify_draft_attn_workspace(_args(page_indices_len=-1)) == 0
     assert fd.fd_verify_draft_attn_workspace(_args(page_indices_len=0)) > 0
