@@ -63,6 +63,9 @@ constexpr int MF_D = 128;
 #ifndef FD_WGS_PER_CU
 #define FD_WGS_PER_CU 2                   // persistent work-groups per compute unit (two fit: registers and LDS)
 #endif
+#ifndef FD_DEFER_T1
+#define FD_DEFER_T1 1
+#endif
 #ifndef FD_KPAD
 #define FD_KPAD 8
 #endif
@@ -558,7 +561,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     fetch_pages(pc, pc.tile0, id0);
     if (pc.nt > 1) fetch_pages(pc, pc.tile0 + 1, id1);
   };
-  auto start_loads = [&](const Piece& pc, const Lane& ln, const int (&id0)[MF_GROUPS], const int (&id1)[MF_GROUPS]) {
+  auto start_loads = [&](const Piece& pc, const Lane& ln, const int (&id0)[MF_GROUPS], const int (&id1)[MF_GROUPS], bool second_tile) {
     const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(pc.s.row0 + (ln.row_valid ? ln.nn : 0)) * p.Hq + ln.hq) * MF_D + 8 * h;
     if (ln.row_valid) {
 #pragma unroll
@@ -569,7 +572,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(zero);
     }
     load_tile(pc, pc.tile0, id0, rA);
-    if (pc.nt > 1) load_tile(pc, pc.tile0 + 1, id1, rB);
+    if (pc.nt > 1 && second_tile) load_tile(pc, pc.tile0 + 1, id1, rB);
     fetch_pages(pc, pc.tile0 + 2, pg);
   };
 
@@ -578,7 +581,15 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   if (!next_piece(cur)) return;
   Lane ln = make_lane(cur);
   if (!PLANNED) start_ids(cur, nid0, nid1);       // (a plan entry brings the first piece's page ids with it)
-  start_loads(cur, ln, nid0, nid1);
+  start_loads(cur, ln, nid0, nid1, !FD_DEFER_T1);
+#if FD_DEFER_T1
+  // Every work-group starts at the same moment: with two tiles each in the first burst (33 MB) the memory
+  // system queues them for 4-5 us and whoever is served last stays behind to the end.  The share's second
+  // tile is requested when the first has landed.
+  int t1ids[MF_GROUPS];
+#pragma unroll
+  for (int j = 0; j < MF_GROUPS; ++j) t1ids[j] = nid1[j];
+#endif
   bool have = true;
   while (have) {
     // descriptor and page ids of the piece after this one: in flight during the tile loop
@@ -610,6 +621,9 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
       for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
     store_tile(0, rA);                             // waits for the piece's first tile
+#if FD_DEFER_T1
+    if (first_piece && nt > 1) load_tile(cur, tile0 + 1, t1ids, rB);
+#endif
     __syncthreads();
 
     // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
@@ -747,7 +761,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
     // ---- next piece: get its loads going before this one is merged and stored --------------
     Lane ln_next = ln;
-    if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1); }
+    if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1, true); }
 
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
     f32x4* xch = reinterpret_cast<f32x4*>(lds);                    // [wave][17][64] quads: 16 of O, then (m, l)
