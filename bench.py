@@ -148,11 +148,15 @@ class Step:
         for i in range(5):
             self.fd.fd_append_kv(args[i % len(args)], *self.pools[i % len(args)], acc, out_len)
         torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        for i, (s, e) in enumerate(evs):
-            s.record(); self.fd.fd_append_kv(args[i % len(args)], *self.pools[i % len(args)], acc, out_len); e.record()
+        # back to back on a busy stream: one event pair around all calls (a lone tiny launch on an idle
+        # stream measures the launch latency from idle, about 10 us, whatever the kernel does)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            self.fd.fd_append_kv(args[i % len(args)], *self.pools[i % len(args)], acc, out_len)
+        e1.record()
         torch.cuda.synchronize()
-        ts = sorted(s.elapsed_time(e) for s, e in evs)
+        ts = [e0.elapsed_time(e1) / steps]
         rows = int((acc + 1).sum().item())
         return {"append_us": round(ts[len(ts) // 2] * 1e3, 2), "append_rows": rows}
 
@@ -253,11 +257,13 @@ def time_select_branch(fd, torch, batch=128, blocks=16, block_len=15, steps=50):
     for _ in range(5):
         fd.fd_select_branch(toks, indptr, nblocks, acc, out, first_vis=fv)
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for s, e in evs:
-        s.record(); fd.fd_select_branch(toks, indptr, nblocks, acc, out, first_vis=fv); e.record()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fd.fd_select_branch(toks, indptr, nblocks, acc, out, first_vis=fv)
+    e1.record()
     torch.cuda.synchronize()
-    ts = sorted(s.elapsed_time(e) for s, e in evs)
+    ts = [e0.elapsed_time(e1) / steps]          # back to back on a busy stream
     return {"batch": B, "blocks": nb, "block_len": mb, "call_us": round(ts[len(ts) // 2] * 1e3, 2)}
 
 
