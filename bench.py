@@ -25,7 +25,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-ATTN_KERNELS = "attn_mfma_kernel (the one kernel of a planned attention call)"
+ATTN_KERNELS = "attn_mfma_kernel + attn_mfma_combine_kernel (every kernel of a planned attention call, one event pair)"
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 COLD_FOOTPRINT = 1.25e9         # bytes of distinct copies a rotating input must span
 LAYERS_PER_PLAN = 36            # Qwen3-8B: one plan (fd_verify_draft_plan) per decoding step serves this many attention calls
@@ -310,15 +310,18 @@ def cpu_baseline(name, budget_s=20.0):
                        f"the {budget_s:.0f} s budget), {spent:.1f} s")
 
 
-def read_traffic(name):
-    """HBM bytes per launch of the streaming kernel from the committed counter summary, if any."""
+def read_profile(name):
+    """Figures of the committed rocprofv3 summaries of this workload (profiles/attn_mfma_<name>_pmc.txt): HBM bytes
+    per launch of the streaming kernel from the FETCH_SIZE / WRITE_SIZE counters, and the streaming and combine
+    kernels' own durations.  Counters and per-kernel timestamps need the profiler, so they cannot be taken live."""
     path = os.path.join(ROOT, "profiles", f"attn_mfma_{name}_pmc.txt")
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            for key in ("traffic_bytes_per_launch", "k1_rocprofv3_avg_us", "k2_rocprofv3_avg_us"):
+                if line.startswith(key + ":"):
+                    out[key] = float(line.split(":")[1])
+    return out
 
 
 def main():
@@ -400,6 +403,8 @@ def main():
     kern_avg_ms = float(np.mean(kern_ms))
     value = st.kv_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = st.kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+    prof = read_profile(args.workload)
+    k1_us = prof.get("k1_rocprofv3_avg_us")
     out = {
         "metric": "verify+draft attn: KV GB/s & % HBM peak; acceptance seqs/s at vocab 151936",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -415,8 +420,11 @@ def main():
         "attn_ms": parts.get("attn"), "accept_ms": parts.get("accept"),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": read_traffic(args.workload), "traffic_source": "committed rocprofv3 --pmc summary under profiles/",
+                     "traffic": prof.get("traffic_bytes_per_launch"),
+                     "traffic_source": "committed rocprofv3 --pmc summary under profiles/",
                      "kernel": ATTN_KERNELS,
+                     "streaming_kernel_alone_us_rocprofv3": k1_us,
+                     "streaming_kernel_alone_frac": round(st.kv_bytes / (k1_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if k1_us else None,
                      "kernel_avg_ms": round(kern_avg_ms, 5), "kernel_min_ms": round(float(np.min(kern_ms)), 5),
                      "kernel_launches_timed": len(kern_ms), "attention_calls_per_plan": LAYERS_PER_PLAN,
                      "mfma_tflops": round(st.flops / (kern_avg_ms * 1e-3) / 1e12, 2)},
