@@ -60,6 +60,9 @@ namespace fd {
 constexpr int MF_BLOCK = 256;
 constexpr int MF_TK = 64;                 // keys per LDS tile
 constexpr int MF_D = 128;
+#ifndef FD_XCDS
+#define FD_XCDS 8                         // accelerator dies of an MI355X; work-groups are dealt to them round-robin
+#endif
 #ifndef FD_WGS_PER_CU
 #define FD_WGS_PER_CU 2                   // persistent work-groups per compute unit (two fit: registers and LDS)
 #endif
@@ -96,11 +99,13 @@ struct MfmaSched {
   int page_shift;
   int group_shift;    // log2(query heads per KV head), -1 if that is not a power of two
   int num_wgs;        // persistent work-groups launched
+  int xcds;           // work-group x runs on XCD x % xcds (1: no such structure is assumed)
+  int reuse;          // != 0: some sequence has several row blocks, i.e. its K/V tiles are read by several items
   int min_share;      // automatic shares are never smaller than this many tiles
   int fixed_share;    // > 0: tiles per work-group asked for by the caller
   unsigned short* part_acc;   // [2 * num_wgs][ROWS_WG][D] fp16: the un-normalised output row divided by its largest magnitude
   float* part_ml;             // [2 * num_wgs][ROWS_WG][4]: running maximum (base 2), row sum, that largest magnitude, unused
-  int4* entries;      // [num_wgs]: the split item that ends in this work-group: (first packed row, head | row block << 16, tile rows, first slot); first < 0: none
+  int4* entries;      // [num_wgs + 1]: entry w: the split item that ends in the work-group of share w: (first packed row, head | row block << 16, tile rows, first slot); first < 0: none.  Entry num_wgs: (shares in use, -, -, -)
   struct PlanEntry* plan;     // [num_wgs]: written by the planning kernel, read by a planned streaming kernel
 };
 
@@ -111,8 +116,8 @@ struct PlanEntry {
   unsigned g0, g1;            // the share: units [g0, g1) of the line
   int L, row0, n, k, v, nb, page0, npages;     // that sequence, clamped as load_seq clamps it
   unsigned sh_q, sh_r;        // share w starts at unit w sh_q + floor(w sh_r / W_eff)
-  int W_eff;                  // work-groups that have a share
-  int pad0;
+  int W_eff;                  // shares in use (valid in every entry, also those without a share)
+  int share;                  // which share this work-group takes
   int pg0[MF_GROUPS], pg1[MF_GROUPS];          // page ids of the first two tiles of the share's first piece
   int pad1[8];
 };
@@ -172,9 +177,16 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 // Where work-group w's share of the line starts.  Every thread of the work-group calls this; the
 // results are uniform.  Tile counts fit 32 bits (the host checks the bound), so no 64-bit division
 // is needed.  share w = [w q + floor(w r / W), ...) with q, r = total / W, total % W: equal to
-// floor(w total / W).  Returns false if the work-group has nothing to do.
+// floor(w total / W).  Returns false if the work-group has nothing to do (W_eff is valid either way).
+//
+// Which share a work-group takes is XCD-aware.  Work-group x of a launch runs on XCD x % 8, each XCD
+// has an L2 of its own, and neighbouring shares of the line often read the same K/V tiles at the same
+// time: the row blocks of one (sequence, KV head) -- items that follow each other on the line -- start
+// together and advance in step.  So the work-groups of one XCD take a CONTIGUOUS run of shares:
+// work-group pw takes share (pw % xcds) * chunk + pw / xcds with chunk = ceil(W_eff / xcds), and the
+// second reader of a tile finds it in its XCD's L2.
 template <int MAXRB>
-__device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched& sc_, int w, int& seq, unsigned& Pt,
+__device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched& sc_, int pw, int& w, int& seq, unsigned& Pt,
                                            SeqInfo& ws, unsigned& g0, unsigned& g1, unsigned& sh_q, unsigned& sh_r,
                                            int& W_eff) {
   constexpr int ROWS_WG = 32 * MAXRB;
@@ -193,9 +205,11 @@ __device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched&
     const unsigned weff = (total + want - 1) / want;
     W_eff = (int)min((unsigned)sc_.num_wgs, weff);
     sh_q = total / (unsigned)W_eff; sh_r = total % (unsigned)W_eff;
+    const int chunk = (W_eff + sc_.xcds - 1) / sc_.xcds;
+    w = pw / sc_.xcds < chunk ? (pw % sc_.xcds) * chunk + pw / sc_.xcds : W_eff;      // W_eff: no share
   };
   auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
-  g0 = 0; g1 = 0; Pt = 0; seq = -1;
+  g0 = 0; g1 = 0; Pt = 0; seq = -1; w = 0;
   if (p.B <= MF_BLOCK) {
     // one pass: thread i keeps sequence i in registers, the owner of tile g0 hands it over through LDS
     SeqInfo s_mine = {}; uint32_t bad = 0; int vt = 0;
@@ -294,17 +308,17 @@ __global__ __launch_bounds__(MF_BLOCK) void attn_mfma_plan_kernel(AttnParams p, 
   constexpr int ROWS_WG = 32 * MAXRB;
   constexpr int MF_START_COST = mf_start_cost(MAXRB);
   const int tid = threadIdx.x;
-  const int w = blockIdx.x;
-  PlanEntry* out = sc_.plan + w;
-  int seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
-  if (!find_share<MAXRB>(p, sc_, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff)) {
-    if (tid == 0) out->seq = -1;
+  const int pw = blockIdx.x;                      // the entry is read by work-group pw of the streaming kernel
+  PlanEntry* out = sc_.plan + pw;
+  int w, seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
+  if (!find_share<MAXRB>(p, sc_, pw, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff)) {
+    if (tid == 0) { out->seq = -1; out->W_eff = W_eff; }
     return;
   }
   // page ids of the first two tiles of the share's first piece (it lies in the item that holds unit g0)
   int T, I; seq_shape(p, ws, ROWS_WG, T, I);
   const int Tu = item_units(T, MF_START_COST);
-  if (Tu <= 0) { if (tid == 0) out->seq = -1; return; }
+  if (Tu <= 0) { if (tid == 0) { out->seq = -1; out->W_eff = W_eff; } return; }
   const int local = (int)(g0 - Pt);
   const int u = local - (local / Tu) * Tu;
   const int tile0 = max(u - MF_START_COST, 0);
@@ -319,7 +333,7 @@ __global__ __launch_bounds__(MF_BLOCK) void attn_mfma_plan_kernel(AttnParams p, 
     out->seq = seq; out->Pt = Pt; out->g0 = g0; out->g1 = g1;
     out->L = ws.L; out->row0 = ws.row0; out->n = ws.n; out->k = ws.k; out->v = ws.v; out->nb = ws.nb;
     out->page0 = ws.page0; out->npages = ws.npages;
-    out->sh_q = sh_q; out->sh_r = sh_r; out->W_eff = W_eff; out->pad0 = 0;
+    out->sh_q = sh_q; out->sh_r = sh_r; out->W_eff = W_eff; out->share = w;
   }
 }
 
@@ -334,34 +348,39 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
-  const int w = blockIdx.x;
+  const int pw = blockIdx.x;
   const bf16_t* Kc = reinterpret_cast<const bf16_t*>(p.k_cache);
   const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
   const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
   const bf16_t* Vn = reinterpret_cast<const bf16_t*>(p.v_new);
-  if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
 
-  int seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
+  int w, seq, W_eff; unsigned Pt, g0, g1, sh_q, sh_r; SeqInfo ws;
   int nid0[MF_GROUPS], nid1[MF_GROUPS];          // page ids of the first two tiles of the piece to start
 #pragma unroll
   for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = 0; nid1[j] = 0; }
   if (PLANNED) {
     // this work-group's plan entry: share, first sequence, first page ids (one scalar load)
-    const int* pe = reinterpret_cast<const int*>(sc_.plan + w);
+    const int* pe = reinterpret_cast<const int*>(sc_.plan + pw);
     seq = sload(pe, 0); Pt = (unsigned)sload(pe, 1);
     g0 = (unsigned)sload(pe, 2); g1 = (unsigned)sload(pe, 3);
     ws.L = sload(pe, 4); ws.row0 = sload(pe, 5); ws.n = sload(pe, 6); ws.k = sload(pe, 7);
     ws.v = sload(pe, 8); ws.nb = sload(pe, 9); ws.page0 = sload(pe, 10); ws.npages = sload(pe, 11);
-    sh_q = (unsigned)sload(pe, 12); sh_r = (unsigned)sload(pe, 13); W_eff = sload(pe, 14);
+    sh_q = (unsigned)sload(pe, 12); sh_r = (unsigned)sload(pe, 13); W_eff = sload(pe, 14); w = sload(pe, 15);
 #pragma unroll
     for (int j = 0; j < MF_GROUPS; ++j) { nid0[j] = sload(pe, 16 + j); nid1[j] = sload(pe, 20 + j); }
     // The plan is trusted to describe these arguments.  The checks below only keep a stale or foreign
     // plan from sending an access outside the caller's buffers (its results are then meaningless).
-    if (seq < 0 || seq >= p.B || W_eff < 1 || W_eff > sc_.num_wgs || w >= W_eff || g1 <= g0 || Pt > g0 || sh_q == 0) return;
+    W_eff = clampi(W_eff, 0, sc_.num_wgs);
+    if (pw == 0 && tid == 0) sc_.entries[sc_.num_wgs] = make_int4(W_eff, 0, 0, 0);       // for the combine kernel
+    if (seq < 0 || seq >= p.B || W_eff < 1 || w < 0 || w >= W_eff || g1 <= g0 || Pt > g0 || sh_q == 0) return;
     clamp_seq(p, ws);
   } else {
-    if (!find_share<MAXRB>(p, sc_, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff)) return;
+    const bool has = find_share<MAXRB>(p, sc_, pw, w, seq, Pt, ws, g0, g1, sh_q, sh_r, W_eff);
+    if (pw == 0 && tid == 0) sc_.entries[sc_.num_wgs] = make_int4(W_eff, 0, 0, 0);
+    if (!has) return;
   }
+  // Slots, entries and every other per-share index below use the share's number w, not blockIdx.x.
+  if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
   auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
   // the work-group whose share holds unit x of the line
   auto wg_of_unit = [&](unsigned x) -> int {
@@ -475,10 +494,18 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, const unsigned (&voff)[4], TileRegs& r) {
     __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
     __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
+    if (sc_.reuse) {                               // the tile has other readers: let the L2 keep it
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 2);      // aux 2: streaming (nt)
-      r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 2);
+      for (int i = 0; i < 4; ++i) {
+        r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 0);
+        r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 2);      // aux 2: streaming (nt), read once
+        r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 2);
+      }
     }
   };
   auto nrec_of = [&](int valid, unsigned pitch) -> int {                 // valid rows of a 16-row group
@@ -864,8 +891,9 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31;                      // a half-wave owns a tile row, a lane four adjacent output columns
   const int* ep = reinterpret_cast<const int*>(sc_.entries + wl);
+  const int shares = sload(reinterpret_cast<const int*>(sc_.entries + sc_.num_wgs), 0);     // entries beyond are nobody's
   const int row0 = sload(ep, 0), head_rt = sload(ep, 1), rows_here = sload(ep, 2), first_slot = sload(ep, 3);
-  if (row0 < 0) return;
+  if (wl >= shares || row0 < 0) return;
   const int trow = blockIdx.y * 8 + wave * 2 + (lane >> 5);
   const int head = head_rt & 0xffff, rt = head_rt >> 16;
   const int wf = first_slot >> 1;
@@ -976,7 +1004,7 @@ size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off
   auto al = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(unsigned short));
   size_t ml = al((size_t)2 * num_wgs * rows_wg * 4 * sizeof(float));
-  size_t en = al((size_t)num_wgs * sizeof(int4));
+  size_t en = al((size_t)(num_wgs + 1) * sizeof(int4));
   size_t pl = al((size_t)num_wgs * sizeof(PlanEntry));
   if (off_ml) *off_ml = acc;
   if (off_entries) *off_entries = acc + ml;
@@ -990,9 +1018,11 @@ static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaS
   sc.group_shift = -1;
   for (int b = 0; b < 16; ++b) if ((1 << b) == p.G) sc.group_shift = b;
   sc.num_wgs = attn_mfma_num_wgs();
+  sc.xcds = sc.num_wgs % FD_XCDS == 0 ? FD_XCDS : 1;
   sc.min_share = 2;
   sc.fixed_share = kv_chunk > 0 ? (kv_chunk + MF_TK - 1) / MF_TK : 0;
   rows_wg = attn_mfma_rows_per_wg(p.max_new_rows * p.G > 128 ? 128 : p.max_new_rows * p.G);
+  sc.reuse = (long long)p.max_new_rows * p.G > rows_wg ? 1 : 0;
   size_t off_ml, off_en, off_pl;
   attn_mfma_workspace(sc.num_wgs, rows_wg, &off_ml, &off_en, &off_pl);
   char* base = reinterpret_cast<char*>(workspace);
