@@ -349,6 +349,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, c32 = lane & 31, l16 = lane & 15;
   const int pw = blockIdx.x;
+  const bool late_wg = pw >= (sc_.num_wgs >> 1);
   const bf16_t* Kc = reinterpret_cast<const bf16_t*>(p.k_cache);
   const bf16_t* Vc = reinterpret_cast<const bf16_t*>(p.v_cache);
   const bf16_t* Kn = reinterpret_cast<const bf16_t*>(p.k_new);
@@ -657,6 +658,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     // (requested earlier) is written to the other LDS buffer and tile t+2 is requested.
     auto iteration = [&](int t, TileRegs& r_store, TileRegs& r_load) {
       const int tau = tile0 + t;
+      // The two work-groups of a CU take turns at the higher wave priority, one tile each.  At equal
+      // priority the older wave wins every contested issue slot, and the CU's second work-group (the
+      // upper half of blockIdx.x: dispatched once every CU has its first) would run about 10 % slower
+      // than the first from start to end.
+      if (((t & 1) != 0) != late_wg) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
       const bf16_t* Ks = lds + (t & 1) * MF_BUF_ELEMS;
       const bf16_t* Vs = Ks + MF_K_ELEMS;
       if (t + 2 < nt) {
