@@ -32,7 +32,7 @@ LAYERS_PER_PLAN = 36            # Qwen3-8B: one plan (fd_verify_draft_plan) per 
 MIN_KERNEL_SAMPLES = 20         # attention launches that are event-bracketed, whatever --steps is
 
 
-ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq_draft", "par4", "par_b1", "par_b2", "q3_1p7b", "q3_14b", "q3_32b"]
+ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq_draft", "par4", "par_b1", "par_b2", "q3_1p7b", "q3_14b", "q3_32b", "d64"]
 
 
 def log(*a):

@@ -108,7 +108,7 @@ typedef struct fd_attn_args {
   int32_t batch;              /* B >= 0                                                       */
   int32_t num_q_heads;        /* Hq, multiple of num_kv_heads                                 */
   int32_t num_kv_heads;       /* Hkv                                                          */
-  int32_t head_dim;           /* D: multiple of 8, <= 128 (MFMA kernel: 128)                  */
+  int32_t head_dim;           /* D: multiple of 8, <= 128 (MFMA kernel: 128 or 64)            */
   int32_t page_size;          /* tokens per page, >= 1 (MFMA kernel: power of two >= 16)      */
   int32_t dtype;              /* fd_dtype                                                     */
   float   sm_scale;           /* 0 => 1/sqrt(head_dim)                                        */
@@ -155,7 +155,7 @@ FD_API fd_status fd_verify_draft_attn(const fd_attn_args *args, void *hip_stream
 /*
  * Planning for fd_verify_draft_attn, separated out because it depends on the lengths only and the
  * same lengths meet every layer of the model in one decoding step (Sec. 4.1: one forward pass
- * verifies and drafts; Sec. 4.3).  The bf16 head_dim-128 kernel cuts the batch's key tiles into
+ * verifies and drafts; Sec. 4.3).  The bf16 kernel for head_dim 128 or 64 cuts the batch's key tiles into
  * equal shares for its persistent work-groups; the plan is, per work-group, where its share
  * starts (sequence, offset, the page ids of its first two tiles).  Without a plan every work-group
  * of fd_verify_draft_attn finds its share itself, by a scan over the batch, before it can request

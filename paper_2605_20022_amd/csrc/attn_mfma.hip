@@ -1,4 +1,4 @@
-// Hybrid-mask verify+draft attention (Sec. 4.1), bf16 MFMA kernel for gfx950, head_dim 128.
+// Hybrid-mask verify+draft attention (Sec. 4.1), bf16 MFMA kernel for gfx950, head_dim 128 or 64.
 //
 // Work decomposition.  An *item* is one (sequence, KV head, block of up to ROWS_WG tile
 // rows); a tile row is (new row, query head of the group), so K and V are read from HBM once
@@ -59,7 +59,7 @@ namespace fd {
 
 constexpr int MF_BLOCK = 256;
 constexpr int MF_TK = 64;                 // keys per LDS tile
-constexpr int MF_D = 128;
+constexpr int MF_D_MAX = 128;             // head dims taken: 128 and 64
 #ifndef FD_XCDS
 #define FD_XCDS 8                         // accelerator dies of an MI355X; work-groups are dealt to them round-robin
 #endif
@@ -75,12 +75,18 @@ constexpr int MF_D = 128;
 #ifndef FD_VPAD
 #define FD_VPAD 32
 #endif
-constexpr int MF_KSTR = MF_D + FD_KPAD;   // K row pitch in bf16 elements (272 bytes)
-constexpr int MF_VSTR = MF_D + FD_VPAD;   // V row pitch (320 bytes): the transposing reads run without bank conflicts (counter-checked; 288 B costs 2 cycles per read)
-constexpr int MF_K_ELEMS = MF_TK * MF_KSTR;
-constexpr int MF_V_ELEMS = MF_TK * MF_VSTR;
-constexpr int MF_BUF_ELEMS = MF_K_ELEMS + MF_V_ELEMS;     // one K+V tile
-constexpr size_t MF_LDS_BYTES = (size_t)2 * MF_BUF_ELEMS * sizeof(bf16_t);   // double buffered
+// LDS layout for head dim DH.  K rows are padded by 16 bytes (pitch 272 B for DH = 128, 144 B for 64: an odd
+// number of 16-byte slots, so the 16 rows a ds_read_b128 touches at once fall into 16 different slots) and
+// V rows by 64 bytes (pitch 320 / 192 B: four consecutive rows start 64 B apart modulo 256, so the 4 rows x 64 B
+// of a transposing read cover every bank once; counter-checked for 128, where a 288 B pitch costs 2 cycles per read).
+template <int DH> struct MfLds {
+  static constexpr int KSTR = DH + FD_KPAD;                // K row pitch in bf16 elements
+  static constexpr int VSTR = DH + FD_VPAD;                // V row pitch
+  static constexpr int K_ELEMS = MF_TK * KSTR;
+  static constexpr int V_ELEMS = MF_TK * VSTR;
+  static constexpr int BUF_ELEMS = K_ELEMS + V_ELEMS;      // one K+V tile
+  static constexpr size_t BYTES = (size_t)2 * BUF_ELEMS * sizeof(bf16_t);   // double buffered
+};
 constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
 constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
 constexpr float MF_LAZY = 6.f;            // the softmax reference follows the row maximum in steps of at least 2^6
@@ -92,7 +98,7 @@ constexpr int mf_start_cost(int maxrb) { return maxrb == 4 ? 2 : 4; }
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-struct TileRegs { u32x4 k[MF_GROUPS]; u32x4 v[MF_GROUPS]; };
+template <int NLD> struct TileRegsT { u32x4 k[NLD]; u32x4 v[NLD]; };      // one wave's 16-key group of a tile: NLD loads per tensor
 
 // Launch-time scheduling parameters and the split-partial storage.
 struct MfmaSched {
@@ -339,9 +345,19 @@ __global__ __launch_bounds__(MF_BLOCK) void attn_mfma_plan_kernel(AttnParams p, 
 
 // Streaming kernel.  MAXRB: 32-row blocks a work-group can own (2: up to 64 tile rows, 4: up to 128).
 // PLANNED: the share comes from the plan entry the planning kernel left, else it is found here.
-template <int MAXRB, bool PLANNED>
+// DH: head dim (128 or 64).
+template <int MAXRB, bool PLANNED, int DH>
 __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int MF_D = DH;
+  constexpr int MF_KSTR = MfLds<DH>::KSTR, MF_VSTR = MfLds<DH>::VSTR;
+  constexpr int MF_K_ELEMS = MfLds<DH>::K_ELEMS, MF_BUF_ELEMS = MfLds<DH>::BUF_ELEMS;
+  constexpr int NST = DH / 16;                   // MFMA steps over the head dim in S = K Q^T
+  constexpr int NDB = DH / 32;                   // 32-wide blocks of the head dim in O
+  constexpr int LPR = DH / 8;                    // lanes that load one row (16 bytes each)
+  constexpr int RPL = 64 / LPR;                  // rows one load instruction of a wave covers
+  constexpr int NLD = 16 / RPL;                  // load instructions per tensor for a wave's 16-key group
+  typedef TileRegsT<NLD> TileRegs;
   constexpr int MF_START_COST = mf_start_cost(MAXRB);
   constexpr int PF_K = FD_PF_K, PF_V = FD_PF_V;   // LDS fragment requests run this many MFMAs ahead
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
@@ -392,9 +408,10 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   };
 
   // Tile loads: wave w fetches the w-th 16-key group of a tile (one page: one base address, one pair
-  // of buffer descriptors per wave and tile); lane l takes 16-byte column l & 15 of keys (l >> 4) + 4 i.
-  const int ld_row = lane >> 4;                // 0..3
-  const int ld_col = (lane & 15) * 8;          // element offset of this lane's 16 bytes
+  // of buffer descriptors per wave and tile); lane l takes 16-byte column l % LPR of keys l / LPR + RPL i
+  // (head dim 128: column l & 15 of keys (l >> 4) + 4 i, four loads per tensor; 64: l & 7, (l >> 3) + 8 i, two).
+  const int ld_row = lane / LPR;
+  const int ld_col = (lane % LPR) * 8;         // element offset of this lane's 16 bytes
   const int page_mask = p.page_size - 1;
   const float cs = p.sm_scale * 1.4426950408889634f;           // scores are kept in base-2 units
 
@@ -459,12 +476,12 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     return false;
   };
 
-  unsigned voff_c[4], voff_n[4];               // byte offsets of this lane's four rows in a cached / a new 16-key group
+  unsigned voff_c[NLD], voff_n[NLD];           // byte offsets of this lane's rows in a cached / a new 16-key group
   const long long new_pitch = (long long)p.Hkv * MF_D;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    voff_c[i] = (unsigned)(2 * ((long long)(ld_row + 4 * i) * p.st + ld_col));
-    voff_n[i] = (unsigned)(2 * ((long long)(ld_row + 4 * i) * new_pitch + ld_col));
+  for (int i = 0; i < NLD; ++i) {
+    voff_c[i] = (unsigned)(2 * ((long long)(ld_row + RPL * i) * p.st + ld_col));
+    voff_n[i] = (unsigned)(2 * ((long long)(ld_row + RPL * i) * new_pitch + ld_col));
   }
 
   // Physical page of each 16-key group of a cached tile: the same for every lane, so they are
@@ -492,18 +509,18 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   // whole work-group.  It is read through a buffer descriptor built in scalar registers (base,
   // size) plus a per-lane 32-bit offset: no vector address arithmetic, and rows past the
   // descriptor's size read as zero.  `nrec` = bytes from the base to the end of the last valid row.
-  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, const unsigned (&voff)[4], TileRegs& r) {
+  auto load_rows = [&](const bf16_t* kbase, const bf16_t* vbase, int nrec, const unsigned (&voff)[NLD], TileRegs& r) {
     __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kbase), 0, nrec, 0x00020000);
     __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vbase), 0, nrec, 0x00020000);
     if (sc_.reuse) {                               // the tile has other readers: let the L2 keep it
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NLD; ++i) {
         r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 0);
         r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 0);
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NLD; ++i) {
         r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, voff[i], 0, 2);      // aux 2: streaming (nt), read once
         r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, voff[i], 0, 2);
       }
@@ -538,8 +555,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     bf16_t* Kb = lds + buf * MF_BUF_ELEMS;
     bf16_t* Vb = Kb + MF_K_ELEMS;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = 16 * wave + ld_row + 4 * i;
+    for (int i = 0; i < NLD; ++i) {
+      const int row = 16 * wave + ld_row + RPL * i;
       *reinterpret_cast<u32x4*>(Kb + row * MF_KSTR + ld_col) = r.k[i];
       *reinterpret_cast<u32x4*>(Vb + row * MF_VSTR + ld_col) = r.v[i];
     }
@@ -575,7 +592,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     return ln;
   };
 
-  bf16x8 qf[8];
+  bf16x8 qf[NST];
   int pg[MF_GROUPS];
 #pragma unroll
   for (int j = 0; j < MF_GROUPS; ++j) pg[j] = 0;
@@ -593,11 +610,11 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     const bf16_t* qp = reinterpret_cast<const bf16_t*>(p.q) + ((long long)(pc.s.row0 + (ln.row_valid ? ln.nn : 0)) * p.Hq + ln.hq) * MF_D + 8 * h;
     if (ln.row_valid) {
 #pragma unroll
-      for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * st));
+      for (int st = 0; st < NST; ++st) qf[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * st));
     } else {
       const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int st = 0; st < 8; ++st) qf[st] = as_bf16x8(zero);
+      for (int st = 0; st < NST; ++st) qf[st] = as_bf16x8(zero);
     }
     load_tile(pc, pc.tile0, id0, rA);
     if (pc.nt > 1 && second_tile) load_tile(pc, pc.tile0 + 1, id1, rB);
@@ -642,9 +659,9 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 
     // ---- running softmax state: one query row per lane ------------------------------------
     float m_run = -INFINITY, l_lane = 0.f;
-    f32x16 o[4];
+    f32x16 o[NDB];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < NDB; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
@@ -684,14 +701,14 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           for (int i = 0; i < 16; ++i) sc[i] = 0.f;
           const bf16_t* kp = Ks + (32 * kb + c32) * MF_KSTR + 8 * h;
           // K fragments are requested PF_K MFMAs before the MFMA that consumes them
-          u32x4 kf[8];
+          u32x4 kf[NST];
 #pragma unroll
           for (int f = 0; f < PF_K; ++f) kf[f] = *reinterpret_cast<const u32x4*>(kp + 16 * f);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int st = 0; st < 8; ++st) {
+          for (int st = 0; st < NST; ++st) {
             sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[st]), qf[st], sc, 0, 0, 0);
-            if (st + PF_K < 8) kf[st + PF_K] = *reinterpret_cast<const u32x4*>(kp + 16 * (st + PF_K));
+            if (st + PF_K < NST) kf[st + PF_K] = *reinterpret_cast<const u32x4*>(kp + 16 * (st + PF_K));
             __builtin_amdgcn_sched_barrier(0);                     // keep the requests where they are written
           }
           return sc;
@@ -730,7 +747,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           if (__any(alpha != 1.f)) {
             l_lane *= alpha;
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < NDB; ++b)
 #pragma unroll
               for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
           }
@@ -745,25 +762,25 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
         };
         // O^T += V^T P^T for block kb
         auto compute_PV = [&](int kb, const unsigned (&pk)[8]) {
-          // V^T fragment pair g: d-block g % 4 of k-step g / 4; keys of a k-step for lane-half h are
+          // V^T fragment pair g: d-block g % NDB of k-step g / NDB; keys of a k-step for lane-half h are
           // base+4h+{0..3} and base+8+4h+{0..3}.  Pairs are requested PF_V MFMAs ahead.
           const bf16_t* vbase = Vs + (32 * kb + 4 * h + (l16 >> 2)) * MF_VSTR + 16 * (c32 >> 4) + 4 * (l16 & 3);
-          s16x4 vf[16];
+          s16x4 vf[4 * NDB];
           auto vread = [&](int g) {
-            const bf16_t* vp = vbase + 16 * (g >> 2) * MF_VSTR + 32 * (g & 3);
+            const bf16_t* vp = vbase + 16 * (g / NDB) * MF_VSTR + 32 * (g % NDB);
             vf[2 * g] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)vp);
             vf[2 * g + 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * MF_VSTR));
           };
 #pragma unroll
           for (int g = 0; g < PF_V; ++g) vread(g);
 #pragma unroll
-          for (int g = 0; g < 8; ++g) {
-            const int q = g >> 2;
+          for (int g = 0; g < 2 * NDB; ++g) {
+            const int q = g / NDB;
             u32x4 pw = {pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]};
             s16x8 vv = {vf[2 * g][0], vf[2 * g][1], vf[2 * g][2], vf[2 * g][3],
                         vf[2 * g + 1][0], vf[2 * g + 1][1], vf[2 * g + 1][2], vf[2 * g + 1][3]};
-            o[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), as_bf16x8(pw), o[g & 3], 0, 0, 0);
-            if (g + PF_V < 8) vread(g + PF_V);
+            o[g % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), as_bf16x8(pw), o[g % NDB], 0, 0, 0);
+            if (g + PF_V < 2 * NDB) vread(g + PF_V);
           }
         };
         auto run_blocks = [&](auto nblk_c, int stride) {
@@ -797,25 +814,27 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
     if (have) { ln_next = make_lane(nxt); start_loads(nxt, ln_next, nid0, nid1, true); }
 
     // ---- merge the waves that shared a row block (through LDS, same register layout) ------
-    f32x4* xch = reinterpret_cast<f32x4*>(lds);                    // [wave][17][64] quads: 16 of O, then (m, l)
+    constexpr int XQ = 4 * NDB;                                    // quads of O per lane
+    f32x4* xch = reinterpret_cast<f32x4*>(lds);                    // [wave][XQ + 1][64] quads: XQ of O, then (m, l)
+    static_assert((size_t)(MF_BLOCK / 64) * (XQ + 1) * 64 * sizeof(f32x4) <= MfLds<DH>::BYTES, "the merge area fits the tile buffers");
     if (MAXRB != 4 && KQ > 1) {
       if (kq > 0 && kq < KQ) {
-        f32x4* dst = xch + (size_t)wave * 17 * 64 + lane;
+        f32x4* dst = xch + (size_t)wave * (XQ + 1) * 64 + lane;
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < NDB; ++b)
 #pragma unroll
           for (int a = 0; a < 4; ++a) {
             f32x4 q4 = {o[b][4 * a], o[b][4 * a + 1], o[b][4 * a + 2], o[b][4 * a + 3]};
             dst[(4 * b + a) * 64] = q4;
           }
         f32x4 ml4 = {m_run, l_lane, 0.f, 0.f};
-        dst[16 * 64] = ml4;
+        dst[XQ * 64] = ml4;
       }
       __syncthreads();
       if (kq == 0) {
         for (int q2 = 1; q2 < KQ; ++q2) {
-          const f32x4* src = xch + (size_t)(rb + q2 * RB) * 17 * 64 + lane;
-          const f32x4 ml4 = src[16 * 64];
+          const f32x4* src = xch + (size_t)(rb + q2 * RB) * (XQ + 1) * 64 + lane;
+          const f32x4 ml4 = src[XQ * 64];
           const float m_o = ml4[0], l_o = ml4[1];
           const float m_new = fmaxf(m_run, m_o);
           const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
@@ -823,7 +842,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           l_lane = l_lane * a + l_o * bsc;
           m_run = m_new;
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4) {
               const f32x4 q4 = src[(4 * b + a4) * 64];
@@ -842,7 +861,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
           bf16_t* op = reinterpret_cast<bf16_t*>(p.out) + ((long long)(s.row0 + nn) * p.Hq + hq) * MF_D + 4 * h;
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
               u32x2 wv = {pack_bf16x2(o[b][4 * a] * inv, o[b][4 * a + 1] * inv),
@@ -856,7 +875,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           // the row's largest entry, a quarter of what the bf16 result carries) plus (max, sum, scale)
           float amax = 0.f;
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(o[b][i]));
           amax = fmaxf(amax, __shfl_xor(amax, 32));
@@ -864,7 +883,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
           const long long ps = (long long)slot * ROWS_WG + trow;
           unsigned short* ap = sc_.part_acc + ps * MF_D + 4 * h;
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
               u32x2 wv = {pack_f16x2(o[b][4 * a] * rs, o[b][4 * a + 1] * rs), pack_f16x2(o[b][4 * a + 2] * rs, o[b][4 * a + 3] * rs)};
@@ -890,9 +909,10 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 // work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 8):
 // half a wave per tile row, a lane owns four adjacent output columns.
 // ---------------------------------------------------------------------------------------
-template <int MAXRB>
+template <int MAXRB, int DH>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
   constexpr int ROWS_WG = 32 * MAXRB;
+  constexpr int MF_D = DH;
   const int wl = blockIdx.x;                      // the work-group in which the split item ended
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31;                      // a half-wave owns a tile row, a lane four adjacent output columns
@@ -904,7 +924,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   const int head = head_rt & 0xffff, rt = head_rt >> 16;
   const int wf = first_slot >> 1;
   if (rows_here > ROWS_WG || first_slot < 0 || wf >= wl || head >= p.Hkv) return;
-  if (trow >= rows_here) return;
+  if (trow >= rows_here || l32 >= MF_D / 4) return;           // (head dim 64: half of the lanes have no column)
   const int T_row = rt * ROWS_WG + trow;
   const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
   if (row0 + nn >= p.total_rows) return;
@@ -980,9 +1000,9 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-// The MFMA kernel takes bf16, head_dim 128 and power-of-two page sizes >= 16.
+// The MFMA kernel takes bf16, head_dim 128 or 64 and power-of-two page sizes >= 16.
 bool attn_mfma_supports(int dtype, int head_dim, int page_size) {
-  return dtype == FD_BF16 && head_dim == MF_D && page_size >= 16 && (page_size & (page_size - 1)) == 0;
+  return dtype == FD_BF16 && (head_dim == 128 || head_dim == 64) && page_size >= 16 && (page_size & (page_size - 1)) == 0;
 }
 
 int attn_mfma_tile_keys() { return MF_TK; }
@@ -1008,7 +1028,7 @@ int attn_mfma_num_wgs() {
 // rows, their (max, sum, scale), the combine entries, the plan entries.
 size_t attn_mfma_workspace(int num_wgs, int rows_wg, size_t* off_ml, size_t* off_entries, size_t* off_plan) {
   auto al = [](size_t x) { return (x + 255) / 256 * 256; };
-  size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D * sizeof(unsigned short));
+  size_t acc = al((size_t)2 * num_wgs * rows_wg * MF_D_MAX * sizeof(unsigned short));      // (sized for head dim 128)
   size_t ml = al((size_t)2 * num_wgs * rows_wg * 4 * sizeof(float));
   size_t en = al((size_t)(num_wgs + 1) * sizeof(int4));
   size_t pl = al((size_t)num_wgs * sizeof(PlanEntry));
@@ -1039,15 +1059,15 @@ static void fill_sched(const AttnParams& p, void* workspace, int kv_chunk, MfmaS
 }
 
 // The streaming kernel's LDS request is above the default limit: raised once per device.
-template <int MAXRB, bool PLANNED>
+template <int MAXRB, bool PLANNED, int DH>
 static hipError_t configure_mfma() {
   static std::atomic<unsigned long long> done{0};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1ull)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<MAXRB, PLANNED>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)MF_LDS_BYTES);
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<MAXRB, PLANNED, DH>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)MfLds<DH>::BYTES);
   if (e == hipSuccess && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
   return e;
 }
@@ -1062,12 +1082,18 @@ hipError_t run_attn_mfma_plan(const AttnParams& p, void* workspace, int kv_chunk
   return hipGetLastError();
 }
 
+template <int MAXRB, bool PLANNED, int DH>
+static hipError_t launch_mfma_d(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
+  hipError_t e = configure_mfma<MAXRB, PLANNED, DH>();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_mfma_kernel<MAXRB, PLANNED, DH>), dim3(sc.num_wgs), dim3(MF_BLOCK), MfLds<DH>::BYTES, st, p, sc);
+  return hipGetLastError();
+}
 template <int MAXRB, bool PLANNED>
 static hipError_t launch_mfma(const AttnParams& p, const MfmaSched& sc, hipStream_t st) {
-  hipError_t e = configure_mfma<MAXRB, PLANNED>();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_mfma_kernel<MAXRB, PLANNED>), dim3(sc.num_wgs), dim3(MF_BLOCK), MF_LDS_BYTES, st, p, sc);
-  return hipGetLastError();
+  if (p.D == 64) return launch_mfma_d<MAXRB, PLANNED, 64>(p, sc, st);
+  if (p.D == 128) return launch_mfma_d<MAXRB, PLANNED, 128>(p, sc, st);
+  return hipErrorInvalidValue;                  // (attn_mfma_supports keeps other head dims away)
 }
 
 // The streaming kernel; planned: the workspace holds the plan for these arguments.
@@ -1082,8 +1108,14 @@ hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, 0, sc, rows_wg);
   dim3 grid(sc.num_wgs, rows_wg / 8);
-  if (rows_wg == 64) hipLaunchKernelGGL(attn_mfma_combine_kernel<2>, grid, dim3(256), 0, st, p, sc);
-  else hipLaunchKernelGGL(attn_mfma_combine_kernel<4>, grid, dim3(256), 0, st, p, sc);
+  if (p.D != 64 && p.D != 128) return hipErrorInvalidValue;
+  if (rows_wg == 64) {
+    if (p.D == 64) hipLaunchKernelGGL((attn_mfma_combine_kernel<2, 64>), grid, dim3(256), 0, st, p, sc);
+    else hipLaunchKernelGGL((attn_mfma_combine_kernel<2, 128>), grid, dim3(256), 0, st, p, sc);
+  } else {
+    if (p.D == 64) hipLaunchKernelGGL((attn_mfma_combine_kernel<4, 64>), grid, dim3(256), 0, st, p, sc);
+    else hipLaunchKernelGGL((attn_mfma_combine_kernel<4, 128>), grid, dim3(256), 0, st, p, sc);
+  }
   return hipGetLastError();
 }
 

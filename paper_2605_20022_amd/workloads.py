@@ -140,6 +140,10 @@ for _name, _hq in (("q3_1p7b", 16), ("q3_14b", 40), ("q3_32b", 64)):     # 4B sh
     CONFIGS[_name] = (AttnWorkload(_name, "bf16", 16, _hq, 8, 128, 16, (512, 4096), (8, 8), 8, _INV_SQRT_128,
                                    seed=BASE_SEED + 2), None)
 
+# A head dim of 64 (the other size the matrix-core kernel takes; 32 / 8 heads with D = 64 is the attention
+# shape of small Llama-3.2-class decoders): cfg3's batch, lengths and paging, entries scaled for D = 64.
+CONFIGS["d64"] = (AttnWorkload("d64", "bf16", 16, 32, 8, 64, 16, (512, 4096), (8, 8), 8, 0.125, seed=BASE_SEED + 2), None)
+
 
 def make_lengths(w: AttnWorkload):
     """Per-sequence lengths and the page table (no tensors).  Deterministic in w.seed."""

@@ -72,15 +72,16 @@ def test_generic_kernel_small_cases(fd, case, dtype):
     dict(B=3, G=5, Hkv=2, ps=16, kv=(30, 700), kr=(1, 9), m=8),            # 5 query heads per KV head (not a power of two)
     dict(B=2, G=3, Hkv=1, ps=16, kv=(0, 260), kr=(0, 30), m=30),           # 3 per KV head, up to 180 tile rows
 ])
-def test_mfma_kernel_small_cases(fd, case):
-    w = _wl("small", "bf16", case["B"], case["G"] * case["Hkv"], case["Hkv"], 128, case["ps"], case["kv"],
+@pytest.mark.parametrize("D", [128, 64])
+def test_mfma_kernel_small_cases(fd, case, D):
+    w = _wl("small", "bf16", case["B"], case["G"] * case["Hkv"], case["Hkv"], D, case["ps"], case["kv"],
             case["kr"], case["m"], seed=21)
     inp = W.make_attention_inputs(w)
     rng = np.random.default_rng(6)
     mv = np.array([rng.integers(0, k + 1) for k in inp["verify_len"]], dtype=np.int32)
     for chunk in (0, 128, 384):
-        _check(fd, inp, "bf16", f"mfma {case} chunk={chunk}", kv_chunk=chunk)
-    _check(fd, inp, "bf16", f"mfma {case} mask_vis", mask_vis=mv, kv_chunk=128)
+        _check(fd, inp, "bf16", f"mfma {case} D={D} chunk={chunk}", kv_chunk=chunk)
+    _check(fd, inp, "bf16", f"mfma {case} D={D} mask_vis", mask_vis=mv, kv_chunk=128)
     # the two kernels are independent implementations: they must also agree with each other
     a, _ = AttnCall(fd, inp, kv_chunk=128).run()
     b, _ = AttnCall(fd, inp, kv_chunk=128, flags=FORCE_GENERIC).run()
@@ -299,9 +300,10 @@ def test_cfg3_ragged_paged_batch(fd):
     _check(fd, sharp, "bf16", "cfg3 sharp")
 
 
-@pytest.mark.parametrize("name", ["q3_1p7b", "q3_14b", "q3_32b"])
+@pytest.mark.parametrize("name", ["q3_1p7b", "q3_14b", "q3_32b", "d64"])
 def test_other_model_shapes(fd, name):
-    """cfg3's ragged paged batch with 2, 5 and 8 query heads per KV head (16, 40, 64 query heads)."""
+    """cfg3's ragged paged batch with 2, 5 and 8 query heads per KV head (16, 40, 64 query heads), and with
+    a head dim of 64."""
     w, _ = W.CONFIGS[name]
     _check(fd, W.make_attention_inputs(w), "bf16", name)
     _check(fd, W.make_attention_inputs(w, std=1.0), "bf16", name + " sharp")
