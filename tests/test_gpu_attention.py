@@ -180,6 +180,26 @@ def test_split_partials_hold_large_values(fd):
     assert np.array_equal(out1, out0 * np.float32(2.0 ** 20))
 
 
+@pytest.mark.parametrize("std", [None, 1.0])
+def test_split_items_are_as_accurate_as_whole_ones(fd, std):
+    """Whether an item is normalised from fp32 accumulators in the work-group that saw all of it, or
+    passes through 16-bit partial rows and the combine kernel, depends on where the share boundaries
+    fall.  The same batch run with shares of two tiles (every item is cut into pieces) and with
+    shares longer than any item (nearly all items whole), every row against the oracle: the split
+    result's largest and root-mean-square errors stay within 10 % of the whole result's."""
+    w = _wl("acc", "bf16", 6, 16, 4, 128, 16, (700, 2600), (4, 8), 8, std=0.0884 if std is None else std, seed=67)
+    inp = W.make_attention_inputs(w)
+    ref, _ = oracle_attention(inp)
+    errs = {}
+    for label, chunk in (("whole", 4096), ("split", 128)):
+        out, _ = AttnCall(fd, inp, kv_chunk=chunk).run()
+        assert_attn_close(out, ref, "bf16", f"accuracy {label} std={std}")
+        d = out.astype(np.float64) - ref
+        errs[label] = (np.abs(d).max(), np.sqrt((d * d).mean()))
+    assert errs["split"][0] <= 1.10 * errs["whole"][0] + 1e-6, errs
+    assert errs["split"][1] <= 1.10 * errs["whole"][1] + 1e-7, errs
+
+
 @pytest.mark.parametrize("name", ["par4", "par_b1", "par_b2"])
 def test_full_parallel_mode_workloads(fd, name):
     """Full parallel mode (Sec. 3; Sec. 4.3: the small-batch default): one candidate block per verify
