@@ -19,12 +19,13 @@
 //
 // Streaming of one tile by the four waves of a work-group:
 //   page ids           scalar loads, one tile ahead (they are uniform across the work-group)
-//   global -> regs     one 16-key group (a 4 KB K slab and a 4 KB V slab of one page) per
-//                      buffer_load_dwordx4, through a buffer descriptor built in scalar
+//   global -> regs     one 16-key group per wave (a 4 KB K slab and a 4 KB V slab of one page at head
+//                      dim 128), buffer_load_dwordx4 through a buffer descriptor built in scalar
 //                      registers: no per-lane address arithmetic, and rows past the end of the
 //                      prefix lie outside the descriptor and read as zero.  Two tiles are in
 //                      flight in registers while a third is multiplied.
-//   regs -> LDS        double buffered, K rows padded to 272 B, V rows to 320 B, one barrier/tile
+//   regs -> LDS        double buffered, K rows padded by 16 B, V rows by 64 B (272 / 320 B at head dim 128),
+//                      one barrier per tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS (ds_read_b128),
 //                      B = Q fragments held in registers for the whole item
 //   online softmax     in the accumulator layout: a lane owns ONE query row (column of
