@@ -93,6 +93,7 @@ def test_mfma_kernel_small_cases(fd, case, D):
     dict(B=3, G=4, Hkv=2, D=128, ps=16, kv=(100, 600), k=4, nb=4, mb=3, dtype="bf16"),
     dict(B=2, G=4, Hkv=1, D=128, ps=16, kv=(300, 900), k=6, nb=3, mb=8, dtype="bf16"),      # pruned hypotheses, 30 rows
     dict(B=2, G=2, Hkv=2, D=64, ps=8, kv=(20, 90), k=3, nb=3, mb=2, dtype="f32"),           # scalar fp32 kernel
+    dict(B=3, G=4, Hkv=2, D=64, ps=16, kv=(100, 700), k=5, nb=5, mb=4, dtype="bf16"),       # head dim 64 on the matrix cores
 ])
 def test_several_mask_blocks(fd, case):
     """One candidate block per hypothetical number of accepted drafts (Sec. 3, parallel
@@ -136,14 +137,15 @@ def test_random_workloads(fd, seed):
     klo = int(rng.integers(0, 4)); khi = klo + int(rng.integers(0, 10))
     nb = int(rng.choice([1, 1, 2, 3])); mb = int(rng.integers(0 if khi > 0 and klo > 0 else 1, 12))
     k_fixed = nb > 1                                        # several blocks: one verify length for all
-    w = W.AttnWorkload("rand", "bf16", B, G * Hkv, Hkv, 128, ps, (lo, hi),
+    D = 64 if seed % 3 == 2 else 128                        # (a draw of its own would move every other seed's case)
+    w = W.AttnWorkload("rand", "bf16", B, G * Hkv, Hkv, D, ps, (lo, hi),
                        (max(khi, 1), max(khi, 1)) if k_fixed else (klo, khi), mb if nb == 1 else max(mb, 1), 1.0,
                        seed=500 + seed, spare_page_frac=0.1, mask_blocks=nb)
     inp = W.make_attention_inputs(w)
     if inp["q"].shape[0] == 0:
         pytest.skip("no new rows drawn")
     chunk = int(rng.choice([0, 0, 64, 192, 512]))
-    what = f"random seed={seed}: B={B} G={G} Hkv={Hkv} ps={ps} kv=({lo},{hi}) k=({klo},{khi}) nb={nb} mb={mb} chunk={chunk}"
+    what = f"random seed={seed}: B={B} G={G} Hkv={Hkv} D={D} ps={ps} kv=({lo},{hi}) k=({klo},{khi}) nb={nb} mb={mb} chunk={chunk}"
     _check(fd, inp, "bf16", what, kv_chunk=chunk)
     if nb == 1:
         mv = np.array([rng.integers(0, k + 1) for k in inp["verify_len"]], dtype=np.int32)
@@ -160,12 +162,13 @@ def test_thousands_of_sequences(fd, B, kv, dtype, flags):
         _check(fd, inp, dtype, f"many B={B} kv={kv} {dtype} flags={flags} chunk={chunk}", kv_chunk=chunk, flags=flags)
 
 
-def test_split_partials_hold_large_values(fd):
+@pytest.mark.parametrize("D", [128, 64])
+def test_split_partials_hold_large_values(fd, D):
     """Items cut across work-groups leave their partial rows in 16 bits, scaled by the row's largest
     entry: values far outside fp16's range must pass through unharmed.  Attention is linear in V and
     a power-of-two factor is exact in every step, so the outputs are those of the unscaled call with
     the exponent moved, bit for bit - and the unscaled call is checked against the oracle."""
-    w = _wl("bigv", "bf16", 3, 8, 2, 128, 16, (300, 900), (2, 6), 5, seed=61)
+    w = _wl("bigv", "bf16", 3, 8, 2, D, 16, (300, 900), (2, 6), 5, seed=61)
     inp = W.make_attention_inputs(w)
     base = _check(fd, inp, "bf16", "large values: unscaled", kv_chunk=128)        # shares of two tiles: every item is split
     out0, _ = AttnCall(fd, inp, kv_chunk=128).run()

@@ -33,6 +33,8 @@ def test_static_scratch_matches_workspace_call_twice(fd):
     _both(fd, W.make_attention_inputs(big))
     _both(fd, W.make_attention_inputs(small))
     _both(fd, W.make_attention_inputs(small), kv_chunk=128)     # every item split: partials everywhere
+    d64 = W.AttnWorkload("st_d64", "bf16", 3, 16, 4, 64, 16, (100, 1500), (2, 8), 8, 1.0, seed=95)            # head dim 64, smaller partial rows
+    _both(fd, W.make_attention_inputs(d64), kv_chunk=128)
     f32 = W.AttnWorkload("st_f32", "f32", 2, 4, 1, 64, 16, (10, 300), (2, 4), 3, 1.0, seed=93)              # the fp32 kernel's workspace fits too
     _both(fd, W.make_attention_inputs(f32))
 
