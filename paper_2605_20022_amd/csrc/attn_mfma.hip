@@ -90,6 +90,8 @@ template <int DH> struct MfLds {
 };
 constexpr int MF_BLOCKS = MF_TK / 32;     // 32-key MFMA blocks per tile
 constexpr int MF_GROUPS = MF_TK / 16;     // 16-key load groups per tile
+constexpr int MF_XCD_TILT = 40;           // per mille of a share that every share of an odd XCD hands to the even XCD before it
+constexpr int MF_TILT_MIN_SHARE = 64;     // ... in launches whose shares are at least this many units long
 constexpr float MF_LAZY = 6.f;            // the softmax reference follows the row maximum in steps of at least 2^6
 // What starting an item costs a work-group, in tile times: measured ≈ 6.9 µs (request the next piece's
 // tiles ≈ 2.4, merge and store ≈ 3.4, wait for the first tile ≈ 1.1) against 2.1 µs per tile in the
@@ -192,6 +194,28 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 // together and advance in step.  So the work-groups of one XCD take a CONTIGUOUS run of shares:
 // work-group pw takes share (pw % xcds) * chunk + pw / xcds with chunk = ceil(W_eff / xcds), and the
 // second reader of a tile finds it in its XCD's L2.
+//
+// The XCDs do not stream at one rate: with every one of them reading its equal part of a long batch, the
+// odd-numbered ones (blockIdx.x odd) finish about 7 % after the even-numbered ones, launch after launch and
+// whichever shares they are given (measured with per-work-group timestamps; whether the two XCDs of a
+// pair share a port to the memory fabric is a guess).  So, on top of the equal cut floor(w total / W),
+// every share of an odd XCD's run hands d = round(MF_XCD_TILT / 1000 of a share) units to the even run
+// before it: boundary i of an even run of a shares, followed by an odd run of b <= a shares, moves up by
+// floor(d b i / a), boundary i of that odd run by d (b - i); the ends of the pair stay where they were.
+// Shares shorter than MF_TILT_MIN_SHARE units are left equal (such launches are not bound by the stream).
+__device__ __forceinline__ unsigned share_begin(const MfmaSched& sc_, int ww, unsigned sh_q, unsigned sh_r, int W_eff) {
+  unsigned g = (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff;
+  if (sc_.xcds > 1 && sh_q >= (unsigned)MF_TILT_MIN_SHARE) {
+    const unsigned d = (sh_q * (unsigned)MF_XCD_TILT + 500u) / 1000u;
+    const int chunk = (W_eff + sc_.xcds - 1) / sc_.xcds;
+    const int run = ww / chunk, i = ww - run * chunk;
+    const int ev = run & ~1;                                             // the even run of this pair
+    const int a = max(0, min(chunk, W_eff - ev * chunk)), b = max(0, min(chunk, W_eff - (ev + 1) * chunk));
+    if (a > 0 && b > 0) g += (run & 1) ? d * (unsigned)(b - i) : (d * (unsigned)b * (unsigned)i) / (unsigned)a;
+  }
+  return g;
+}
+
 template <int MAXRB>
 __device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched& sc_, int pw, int& w, int& seq, unsigned& Pt,
                                            SeqInfo& ws, unsigned& g0, unsigned& g1, unsigned& sh_q, unsigned& sh_r,
@@ -215,7 +239,7 @@ __device__ __forceinline__ bool find_share(const AttnParams& p, const MfmaSched&
     const int chunk = (W_eff + sc_.xcds - 1) / sc_.xcds;
     w = pw / sc_.xcds < chunk ? (pw % sc_.xcds) * chunk + pw / sc_.xcds : W_eff;      // W_eff: no share
   };
-  auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
+  auto share_start = [&](int ww) -> unsigned { return share_begin(sc_, ww, sh_q, sh_r, W_eff); };
   g0 = 0; g1 = 0; Pt = 0; seq = -1; w = 0;
   if (p.B <= MF_BLOCK) {
     // one pass: thread i keeps sequence i in registers, the owner of tile g0 hands it over through LDS
@@ -399,7 +423,7 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
   }
   // Slots, entries and every other per-share index below use the share's number w, not blockIdx.x.
   if (tid == 0) sc_.entries[w] = make_int4(-1, 0, 0, 0);
-  auto share_start = [&](int ww) -> unsigned { return (unsigned)ww * sh_q + ((unsigned)ww * sh_r) / (unsigned)W_eff; };
+  auto share_start = [&](int ww) -> unsigned { return share_begin(sc_, ww, sh_q, sh_r, W_eff); };
   // the work-group whose share holds unit x of the line
   auto wg_of_unit = [&](unsigned x) -> int {
     int ww = (int)min(x / max(sh_q, 1u), (unsigned)(W_eff - 1));
