@@ -22,8 +22,8 @@
 //   global -> regs     one 16-key group per wave (a 4 KB K slab and a 4 KB V slab of one page at head
 //                      dim 128), buffer_load_dwordx4 through a buffer descriptor built in scalar
 //                      registers: no per-lane address arithmetic, and rows past the end of the
-//                      prefix lie outside the descriptor and read as zero.  Two tiles are in
-//                      flight in registers while a third is multiplied.
+//                      prefix lie outside the descriptor and read as zero.  Two tiles are held
+//                      in registers while a third is multiplied.
 //   regs -> LDS        double buffered, K rows padded by 16 B, V rows by 64 B (272 / 320 B at head dim 128),
 //                      one barrier per tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS (ds_read_b128),
@@ -696,8 +696,12 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 #endif
     __syncthreads();
 
-    // Two tiles are kept in flight in registers: while tile t is multiplied out of LDS, tile t+1
-    // (requested earlier) is written to the other LDS buffer and tile t+2 is requested.
+    // Two tiles are kept in registers: while tile t is multiplied out of LDS, tile t+2 is requested and
+    // tile t+1 (requested an iteration earlier) is written to the other LDS buffer.  The request is
+    // conditional and comes in two cache-policy variants, so the compiler's wait before that write
+    // cannot count on it and drains the whole queue, tile t+2's loads included: the stream is in effect
+    // one and a half tiles deep.  Making it exactly two deep was measured and is slower (more requests in
+    // flight lengthen every queue, and a work-group that is behind falls further behind).
     auto iteration = [&](int t, TileRegs& r_store, TileRegs& r_load) {
       const int tau = tile0 + t;
       // The two work-groups of a CU take turns at the higher wave priority, one tile each.  At equal
