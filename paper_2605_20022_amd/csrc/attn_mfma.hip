@@ -935,8 +935,8 @@ __global__ __launch_bounds__(MF_BLOCK, 2) void attn_mfma_kernel(AttnParams p, Mf
 // Merge the split partials of every item that was cut by a share boundary:
 //   M = max m;  out = sum 2^{m - M} acc / sum 2^{m - M} l;  lse = (M + log2 sum) ln 2.
 // The pieces of an item sit in its first slot, then in the first slot (2w) of every later
-// work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 8):
-// half a wave per tile row, a lane owns four adjacent output columns.
+// work-group up to the one it ended in (which left the entry).  grid (num_wgs, ROWS_WG / 16):
+// sixteen lanes per tile row, a lane owns eight adjacent output columns.
 // ---------------------------------------------------------------------------------------
 template <int MAXRB, int DH>
 __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, MfmaSched sc_) {
@@ -944,16 +944,16 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   constexpr int MF_D = DH;
   const int wl = blockIdx.x;                      // the work-group in which the split item ended
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31;                      // a half-wave owns a tile row, a lane four adjacent output columns
+  const int l16 = lane & 15;                      // sixteen lanes own a tile row, a lane eight adjacent output columns
   const int* ep = reinterpret_cast<const int*>(sc_.entries + wl);
   const int shares = sload(reinterpret_cast<const int*>(sc_.entries + sc_.num_wgs), 0);     // entries beyond are nobody's
   const int row0 = sload(ep, 0), head_rt = sload(ep, 1), rows_here = sload(ep, 2), first_slot = sload(ep, 3);
   if (wl >= shares || row0 < 0) return;
-  const int trow = blockIdx.y * 8 + wave * 2 + (lane >> 5);
+  const int trow = blockIdx.y * 16 + wave * 4 + (lane >> 4);
   const int head = head_rt & 0xffff, rt = head_rt >> 16;
   const int wf = first_slot >> 1;
   if (rows_here > ROWS_WG || first_slot < 0 || wf >= wl || head >= p.Hkv) return;
-  if (trow >= rows_here || l32 >= MF_D / 4) return;           // (head dim 64: half of the lanes have no column)
+  if (trow >= rows_here || l16 >= MF_D / 8) return;           // (head dim 64: half of the lanes have no column)
   const int T_row = rt * ROWS_WG + trow;
   const int nn = T_row / p.G, hq = head * p.G + T_row % p.G;
   if (row0 + nn >= p.total_rows) return;
@@ -962,24 +962,27 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
     return reinterpret_cast<const f32x4*>(sc_.part_ml + (slot * ROWS_WG + trow) * 4);
   };
-  auto acc_of = [&](int pi) -> const u32x2* {               // four fp16 columns of the scaled row
+  auto acc_of = [&](int pi) -> const u32x4* {               // eight fp16 columns of the scaled row
     const long long slot = pi == 0 ? first_slot : 2 * (wf + pi);
-    return reinterpret_cast<const u32x2*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + l32;
+    return reinterpret_cast<const u32x4*>(sc_.part_acc + (slot * ROWS_WG + trow) * MF_D) + l16;
   };
-  f32x4 num = {0.f, 0.f, 0.f, 0.f};
+  float num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float den = 0.f, M = -INFINITY;
-  auto add_piece = [&](const f32x4& ml, const u32x2& a) {
+  auto add_piece = [&](const f32x4& ml, const u32x4& a) {
     const float wgt = ml[0] == -INFINITY ? 0.f : exp2f(ml[0] - M);
     const float wa = wgt * ml[2];
-    float x[4]; unpack_f16x4(a, x);
+    float x[8];
+    { u32x2 lo = {a[0], a[1]}, hi = {a[2], a[3]}; float xl[4], xh[4]; unpack_f16x4(lo, xl); unpack_f16x4(hi, xh);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) num[e] = fmaf(wa, x[e], num[e]);
+      for (int e = 0; e < 4; ++e) { x[e] = xl[e]; x[4 + e] = xh[e]; } }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) num[e] = fmaf(wa, x[e], num[e]);
     den = fmaf(wgt, ml[1], den);
   };
   // up to 24 pieces: everything is requested at once (one memory latency), then reduced
   auto merge_at_once = [&](auto n_c) {
     constexpr int N = decltype(n_c)::value;
-    f32x4 ml[N]; u32x2 a[N];
+    f32x4 ml[N]; u32x4 a[N];
 #pragma unroll
     for (int u = 0; u < N; ++u) {
       const int pu = min(u, np - 1);
@@ -998,7 +1001,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
     // a very long item spread over more work-groups than that: eight at a time, all of a batch
     // requested together, with a running maximum (the sums are rescaled when it grows)
     for (int p0 = 0; p0 < np; p0 += 8) {
-      f32x4 ml[8]; u32x2 a[8];
+      f32x4 ml[8]; u32x4 a[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int pu = min(p0 + u, np - 1);
@@ -1011,7 +1014,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
       if (Mb > M) {
         const float r = M == -INFINITY ? 0.f : exp2f(M - Mb);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) num[e] *= r;
+        for (int e = 0; e < 8; ++e) num[e] *= r;
         den *= r;
         M = Mb;
       }
@@ -1021,9 +1024,10 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   }
   const float inv = den > 0.f ? 1.0f / den : 0.f;
   const long long orow = (long long)(row0 + nn) * p.Hq + hq;
-  u32x2 packed = {pack_bf16x2(num[0] * inv, num[1] * inv), pack_bf16x2(num[2] * inv, num[3] * inv)};
-  reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(p.out) + orow * MF_D)[l32] = packed;
-  if (p.lse && l32 == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
+  u32x4 packed = {pack_bf16x2(num[0] * inv, num[1] * inv), pack_bf16x2(num[2] * inv, num[3] * inv),
+                  pack_bf16x2(num[4] * inv, num[5] * inv), pack_bf16x2(num[6] * inv, num[7] * inv)};
+  reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.out) + orow * MF_D)[l16] = packed;
+  if (p.lse && l16 == 0) p.lse[orow] = (M + log2f(den)) * 0.6931471805599453f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1136,7 +1140,7 @@ hipError_t run_attn_mfma(const AttnParams& p, void* workspace, int kv_chunk, boo
 hipError_t run_attn_mfma_combine(const AttnParams& p, void* workspace, hipStream_t st) {
   MfmaSched sc; int rows_wg;
   fill_sched(p, workspace, 0, sc, rows_wg);
-  dim3 grid(sc.num_wgs, rows_wg / 8);
+  dim3 grid(sc.num_wgs, rows_wg / 16);
   if (p.D != 64 && p.D != 128) return hipErrorInvalidValue;
   if (rows_wg == 64) {
     if (p.D == 64) hipLaunchKernelGGL((attn_mfma_combine_kernel<2, 64>), grid, dim3(256), 0, st, p, sc);
