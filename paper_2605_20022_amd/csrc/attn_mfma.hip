@@ -979,7 +979,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
     for (int e = 0; e < 8; ++e) num[e] = fmaf(wa, x[e], num[e]);
     den = fmaf(wgt, ml[1], den);
   };
-  // up to 24 pieces: everything is requested at once (one memory latency), then reduced
+  // up to 12 pieces: everything is requested at once (one memory latency), then reduced
   auto merge_at_once = [&](auto n_c) {
     constexpr int N = decltype(n_c)::value;
     f32x4 ml[N]; u32x4 a[N];
@@ -989,6 +989,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
       ml[u] = *ml_of(pu); a[u] = *acc_of(pu);
       if (u >= np) ml[u][0] = -INFINITY;
     }
+    __builtin_amdgcn_sched_barrier(0);             // every request goes out before the first result is used
 #pragma unroll
     for (int u = 0; u < N; ++u) M = fmaxf(M, ml[u][0]);
 #pragma unroll
@@ -996,21 +997,25 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
   };
   if (np <= 4) merge_at_once(std::integral_constant<int, 4>{});
   else if (np <= 8) merge_at_once(std::integral_constant<int, 8>{});
-  else if (np <= 24) merge_at_once(std::integral_constant<int, 24>{});
+  else if (np <= 12) merge_at_once(std::integral_constant<int, 12>{});
   else {
-    // a very long item spread over more work-groups than that: eight at a time, all of a batch
-    // requested together, with a running maximum (the sums are rescaled when it grows)
-    for (int p0 = 0; p0 < np; p0 += 8) {
-      f32x4 ml[8]; u32x4 a[8];
+    // an item spread over more work-groups than that (cfg5: 17-18): twelve pieces at a time, all of a
+    // batch requested together, with a running maximum (the sums are rescaled when it grows).  Larger
+    // batches would need more registers than four blocks per CU leave, and most blocks of this grid
+    // only look at their entry and return: how many of them a CU holds at once sets the kernel's floor.
+    constexpr int NB = 12;
+    for (int p0 = 0; p0 < np; p0 += NB) {
+      f32x4 ml[NB]; u32x4 a[NB];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < NB; ++u) {
         const int pu = min(p0 + u, np - 1);
         ml[u] = *ml_of(pu); a[u] = *acc_of(pu);
         if (p0 + u >= np) ml[u][0] = -INFINITY;
       }
+      __builtin_amdgcn_sched_barrier(0);
       float Mb = M;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) Mb = fmaxf(Mb, ml[u][0]);
+      for (int u = 0; u < NB; ++u) Mb = fmaxf(Mb, ml[u][0]);
       if (Mb > M) {
         const float r = M == -INFINITY ? 0.f : exp2f(M - Mb);
 #pragma unroll
@@ -1019,7 +1024,7 @@ __global__ __launch_bounds__(256) void attn_mfma_combine_kernel(AttnParams p, Mf
         M = Mb;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) add_piece(ml[u], a[u]);
+      for (int u = 0; u < NB; ++u) add_piece(ml[u], a[u]);
     }
   }
   const float inv = den > 0.f ? 1.0f / den : 0.f;
